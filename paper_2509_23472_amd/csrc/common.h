@@ -1,0 +1,111 @@
+// Shared device helpers, launch bookkeeping and per-kernel event profiling.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <string.h>
+
+#include <map>
+#include <string>
+#include <vector>
+
+#include "../../include/loract.h"
+
+typedef __bf16 bf16_t;
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+
+// Element kinds used by the runtime-typed kernels (values match loract_dtype where they overlap).
+enum { EK_F32 = 0, EK_BF16 = 1, EK_F64 = 2 };
+
+__host__ __device__ inline int ek_size(int ek) { return ek == EK_F64 ? 8 : (ek == EK_F32 ? 4 : 2); }
+
+__device__ inline double load_f64(const void* p, int64_t i, int ek) {
+  if (ek == EK_F32) return (double)((const float*)p)[i];
+  if (ek == EK_F64) return ((const double*)p)[i];
+  return (double)(float)((const bf16_t*)p)[i];
+}
+__device__ inline void store_f64(void* p, int64_t i, int ek, double v) {
+  if (ek == EK_F32) ((float*)p)[i] = (float)v;
+  else if (ek == EK_F64) ((double*)p)[i] = v;
+  else ((bf16_t*)p)[i] = (bf16_t)(float)v;
+}
+
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// ---------------------------------------------------------------------------------------------
+// Error state and profiling (host side).
+
+struct LoractHostState {
+  std::string last_hip_error;
+};
+static thread_local LoractHostState g_host;
+
+static inline int hip_fail(hipError_t e, const char* what) {
+  g_host.last_hip_error = std::string(what) + ": " + hipGetErrorString(e);
+  return LORACT_ERR_HIP;
+}
+
+struct ProfRecord {
+  const char* name;
+  hipEvent_t start, stop;
+};
+struct ProfState {
+  bool on = false;
+  std::vector<ProfRecord> recs;
+  std::vector<hipEvent_t> pool;
+  std::map<std::string, std::pair<double, int64_t>> agg;
+  std::vector<std::string> order;
+};
+static ProfState g_prof;
+
+static inline hipEvent_t prof_event() {
+  hipEvent_t e;
+  if (!g_prof.pool.empty()) {
+    e = g_prof.pool.back();
+    g_prof.pool.pop_back();
+    return e;
+  }
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+struct KernelScope {
+  hipStream_t stream;
+  hipEvent_t start = nullptr, stop = nullptr;
+  const char* name;
+  KernelScope(const char* n, hipStream_t s) : stream(s), name(n) {
+    if (g_prof.on) {
+      start = prof_event();
+      stop = prof_event();
+      if (start) (void)hipEventRecord(start, stream);
+    }
+  }
+  ~KernelScope() {
+    if (start && stop) {
+      (void)hipEventRecord(stop, stream);
+      g_prof.recs.push_back({name, start, stop});
+    }
+  }
+};
+
+// Launch `kernel<<<grid, block, shmem, stream>>>(args...)`, timing it when profiling is on,
+// and turn a launch failure into LORACT_ERR_HIP.
+#define LORACT_LAUNCH(NAME, STREAM, KERNEL, GRID, BLOCK, SHMEM, ...)                      \
+  do {                                                                                    \
+    {                                                                                     \
+      KernelScope scope_(NAME, STREAM);                                                   \
+      hipLaunchKernelGGL(KERNEL, GRID, BLOCK, SHMEM, STREAM, __VA_ARGS__);                \
+    }                                                                                     \
+    hipError_t e_ = hipGetLastError();                                                    \
+    if (e_ != hipSuccess) return hip_fail(e_, NAME);                                      \
+  } while (0)
+
+#define LORACT_TRY(EXPR)              \
+  do {                                \
+    int rc_ = (EXPR);                 \
+    if (rc_ != LORACT_OK) return rc_; \
+  } while (0)

@@ -1,0 +1,475 @@
+// libloract: C ABI entry points and host-side orchestration.  See include/loract.h.
+#include "common.h"
+#include "gemm_bf16.h"
+#include "gemm_f64.h"
+#include "chol.h"
+
+#include <algorithm>
+#include <cmath>
+#include <set>
+
+// ---------------------------------------------------------------------------------------------
+// Small utility kernels.
+
+struct IdxPack {
+  int32_t v[LORACT_MAX_RANK];
+};
+
+// Copies the sampled row ids (passed by value in the kernel arguments, so no host-to-device
+// copy is needed) into the workspace and clears the status word.
+__global__ void store_indices_kernel(IdxPack pack, int count, int32_t* dst, int32_t* status) {
+  const int t = blockIdx.x * blockDim.x + threadIdx.x;
+  if (t < count) dst[t] = pack.v[t];
+  if (t == 0 && status) *status = 0;
+}
+
+__global__ __launch_bounds__(256) void convert_kernel(const void* src, int src_ek, void* dst,
+                                                      int dst_ek, int64_t count) {
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < count;
+       i += (int64_t)gridDim.x * blockDim.x)
+    store_f64(dst, i, dst_ek, load_f64(src, i, src_ek));
+}
+
+static int launch_convert(hipStream_t s, const void* src, int src_ek, void* dst, int dst_ek,
+                          int64_t count) {
+  if (count <= 0) return LORACT_OK;
+  int blocks = (int)std::min<int64_t>(ceil_div64(count, 256), 4096);
+  LORACT_LAUNCH("convert", s, convert_kernel, dim3(blocks), dim3(256), 0, src, src_ek, dst, dst_ek,
+                count);
+  return LORACT_OK;
+}
+
+// splitmix64: state += golden; output = mix(state).
+__host__ __device__ inline uint64_t splitmix64_mix(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+#define SPLITMIX_GOLDEN 0x9E3779B97F4A7C15ull
+
+__global__ __launch_bounds__(256) void gaussian_kernel(void* dst, int ek, int64_t count,
+                                                       uint64_t seed) {
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < count;
+       e += (int64_t)gridDim.x * blockDim.x) {
+    const uint64_t h = splitmix64_mix(seed + (uint64_t)(e + 1) * SPLITMIX_GOLDEN);
+    const double u1 = ((double)(uint32_t)(h >> 32) + 1.0) * (1.0 / 4294967296.0);
+    const double u2 = (double)(uint32_t)(h & 0xFFFFFFFFull) * (1.0 / 4294967296.0);
+    const double z = sqrt(-2.0 * log(u1)) * cospi(2.0 * u2);
+    store_f64(dst, e, ek, z);
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host helpers.
+
+static bool dtype_ok(int d) { return d == LORACT_F32 || d == LORACT_BF16; }
+
+static int sample_indices_host(int64_t m, int32_t l, uint64_t seed, int32_t* out) {
+  if (!out || l < 0 || m < 0 || l > m || m > 0x7fffffffLL) return LORACT_ERR_INVALID_ARG;
+  std::set<int64_t> chosen;
+  uint64_t state = seed;
+  for (int64_t i = m - l; i < m; ++i) {
+    state += SPLITMIX_GOLDEN;
+    const uint64_t r = splitmix64_mix(state);
+    const int64_t j = (int64_t)(r % (uint64_t)(i + 1));
+    if (!chosen.insert(j).second) chosen.insert(i);
+  }
+  int32_t c = 0;
+  for (int64_t v : chosen) out[c++] = (int32_t)v;
+  return LORACT_OK;
+}
+
+// Workspace layout shared by loract_compress and loract_rsvd.
+struct Plan {
+  int bf16_path;
+  int l;                 // sketch columns
+  int gram_splits, proj_splits;
+  size_t off_idx, off_a, off_b, off_ub, off_g, off_rinv, off_dpart, off_fpart, off_zt;
+  size_t off_bmat, off_eig, off_omega;
+  size_t total;
+};
+
+static int pick_splits(int64_t tiles, int64_t K, int64_t min_k_per_split) {
+  int64_t s = std::max<int64_t>(1, 1024 / std::max<int64_t>(1, tiles));
+  s = std::min<int64_t>(s, std::max<int64_t>(1, K / min_k_per_split));
+  return (int)std::min<int64_t>(s, 64);
+}
+
+static int validate_params(const loract_params* p, bool rsvd, int* l_out) {
+  if (!p) return LORACT_ERR_INVALID_ARG;
+  if (p->m < 1 || p->n < 1 || p->ldx < p->n || p->k < 1 || p->t < 0) return LORACT_ERR_INVALID_ARG;
+  if (p->m > 0x7fffffffLL || p->n > 0x7fffffffLL) return LORACT_ERR_INVALID_ARG;
+  if (!dtype_ok(p->x_dtype) || !dtype_ok(p->factor_dtype)) return LORACT_ERR_INVALID_ARG;
+  if (p->k > p->m || p->k > p->n) return LORACT_ERR_INVALID_ARG;
+  int l = p->l == 0 ? p->k : p->l;
+  if (rsvd) {
+    if (l < p->k || l > p->m || l > p->n) return LORACT_ERR_INVALID_ARG;
+  } else if (l != p->k) {
+    return LORACT_ERR_NOT_IMPLEMENTED;   // sampling more rows than the rank is not part of Algorithm 1
+  }
+  if (l > LORACT_MAX_RANK) return LORACT_ERR_UNSUPPORTED;
+  if (p->x_dtype == LORACT_F32 && p->factor_dtype != LORACT_F32) return LORACT_ERR_UNSUPPORTED;
+  *l_out = l;
+  return LORACT_OK;
+}
+
+static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
+  int l = 0;
+  LORACT_TRY(validate_params(p, rsvd, &l));
+  pl->l = l;
+  pl->bf16_path = (p->x_dtype == LORACT_BF16);
+  const int64_t m = p->m, n = p->n;
+  const size_t ybytes = (size_t)m * l * (pl->bf16_path ? 4 : 8);
+  const int64_t lt = ceil_div64(l, 64);
+  pl->gram_splits = pick_splits(lt * lt, m, 256);
+  pl->proj_splits = pick_splits(lt * ceil_div64(n, 64), m, 256);
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  pl->off_idx = take(sizeof(int32_t) * LORACT_MAX_RANK);
+  pl->off_a = take(ybytes);
+  pl->off_b = take(ybytes);
+  pl->off_ub = take(pl->bf16_path ? (size_t)m * l * 2 : 0);
+  pl->off_g = take((size_t)l * l * 8);
+  pl->off_rinv = take((size_t)l * l * 8);
+  size_t dpart = (size_t)pl->gram_splits * l * l * 8;
+  if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
+  pl->off_dpart = take(dpart);
+  pl->off_fpart = take(pl->bf16_path ? (size_t)pl->proj_splits * l * n * 4 : 0);
+  const bool need_zt = p->t > 0 || rsvd;
+  pl->off_zt = take(need_zt ? (size_t)l * n * (pl->bf16_path ? 2 : 8) : 0);
+  pl->off_bmat = take(rsvd && l > p->k ? (size_t)l * n * (pl->bf16_path ? 4 : 8) : 0);
+  pl->off_eig = take(rsvd && l > p->k ? (size_t)3 * l * l * 8 : 0);
+  pl->off_omega = take(rsvd ? (size_t)l * n * (pl->bf16_path ? 2 : 4) : 0);
+  pl->total = off;
+  return LORACT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Building blocks of Algorithm 1 on the device.
+
+struct Ctx {
+  hipStream_t s;
+  const loract_params* p;
+  Plan pl;
+  char* ws;
+  int32_t* status;
+  const void* X;
+  int x_ek;      // element kind of X
+  int y_ek;      // element kind of the sketch / Q work buffers (fp32 on the bf16 path, fp64 otherwise)
+};
+
+template <typename T>
+static T* ws_ptr(const Ctx& c, size_t off) { return (T*)(c.ws + off); }
+
+// Y (m x l) = X * Bt^T where Bt is l x n, K-contiguous rows of length n (optionally gathered
+// from X itself through the sampled row ids).  Algorithm 1, step 2 and the second half of step 5.
+static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows, void* Y) {
+  const int64_t m = c.p->m, n = c.p->n;
+  const int l = c.pl.l;
+  if (c.pl.bf16_path)
+    return launch_gemm_bf16("sketch", c.s, (const bf16_t*)c.X, c.p->ldx, 1, (const bf16_t*)Bt, ldb,
+                            1, rows, m, l, n, Y, l, EK_F32, 1, nullptr);
+  return launch_gemm_f64("sketch_f64", c.s, c.X, c.p->ldx, 1, EK_F32, Bt, ldb, 1,
+                         rows ? EK_F32 : EK_F64, rows, m, l, n, 1.0, Y, l, EK_F64, 1, nullptr);
+}
+
+// Thin QR of Y (m x l) by two rounds of Cholesky QR with float64 Gram matrices (steps 4 and 7
+// of Algorithm 1).  Y is overwritten; the orthonormal factor is written to Qout (element kind
+// q_ek, leading dimension l).  `tmp` is a second m x l work buffer of Y's element kind.
+static int orthonormalise(const Ctx& c, void* Y, void* tmp, void* Qout, int q_ek) {
+  const int64_t m = c.p->m;
+  const int l = c.pl.l;
+  double* G = ws_ptr<double>(c, c.pl.off_g);
+  double* Rinv = ws_ptr<double>(c, c.pl.off_rinv);
+  double* dpart = ws_ptr<double>(c, c.pl.off_dpart);
+  const void* src = Y;
+  for (int round = 0; round < 2; ++round) {
+    LORACT_TRY(launch_gemm_f64("gram", c.s, src, l, 0, c.y_ek, src, l, 0, c.y_ek, nullptr, l, l, m,
+                               1.0, G, l, EK_F64, c.pl.gram_splits, dpart));
+    // first round shifted by ~8 max(l, sqrt(m)) u trace(G), second round plain (see chol.h)
+    const double shift_rel =
+        round == 0 ? 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16 : 0.0;
+    LORACT_TRY(launch_chol_inverse(c.s, G, Rinv, l, shift_rel, c.status));
+    void* dst = round == 0 ? tmp : Qout;
+    const int dst_ek = round == 0 ? c.y_ek : q_ek;
+    LORACT_TRY(launch_gemm_f64("apply_rinv", c.s, src, l, 1, c.y_ek, Rinv, l, 0, EK_F64, nullptr, m,
+                               l, l, 1.0, dst, l, dst_ek, 1, nullptr));
+    src = dst;
+  }
+  return LORACT_OK;
+}
+
+// Bt (l x n) = Q^T X: step 8 of Algorithm 1 (and the first half of step 5).
+static int project(const Ctx& c, const void* Q, int q_ek, void* Bt, int out_ek) {
+  const int64_t m = c.p->m, n = c.p->n;
+  const int l = c.pl.l;
+  if (c.pl.bf16_path)
+    return launch_gemm_bf16("project", c.s, (const bf16_t*)Q, l, 0, (const bf16_t*)c.X, c.p->ldx, 0,
+                            nullptr, l, n, m, Bt, n, out_ek, c.pl.proj_splits,
+                            ws_ptr<float>(c, c.pl.off_fpart));
+  return launch_gemm_f64("project_f64", c.s, Q, l, 0, q_ek, c.X, c.p->ldx, 0, EK_F32, nullptr, l, n,
+                         m, 1.0, Bt, n, out_ek, c.pl.proj_splits, ws_ptr<double>(c, c.pl.off_dpart));
+}
+
+static int check_common(const void* X, const loract_params* p, void* U, void* V, void* ws,
+                        size_t ws_bytes, bool rsvd, Ctx* c, hipStream_t s, int32_t* status) {
+  if (!X || !U || !V) return LORACT_ERR_INVALID_ARG;
+  LORACT_TRY(make_plan(p, rsvd, &c->pl));
+  if (!ws || ws_bytes < c->pl.total) return LORACT_ERR_WORKSPACE_TOO_SMALL;
+  if (((uintptr_t)ws) % 16 != 0) return LORACT_ERR_INVALID_ARG;
+  c->s = s;
+  c->p = p;
+  c->ws = (char*)ws;
+  c->status = status;
+  c->X = X;
+  c->x_ek = p->x_dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
+  c->y_ek = c->pl.bf16_path ? EK_F32 : EK_F64;
+  return LORACT_OK;
+}
+
+// Final orthonormalisation + projection shared by compress and the l == k case of rsvd:
+// leaves U (m x l, factor dtype) and V (l x n, factor dtype).
+static int finish_factors(const Ctx& c, void* Y, void* tmp, void* U, void* V) {
+  const int64_t m = c.p->m;
+  const int l = c.pl.l;
+  const int f_ek = c.p->factor_dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
+  if (c.pl.bf16_path) {
+    bf16_t* Ub = (bf16_t*)U;
+    if (f_ek == EK_BF16) {
+      LORACT_TRY(orthonormalise(c, Y, tmp, U, EK_BF16));
+    } else {
+      LORACT_TRY(orthonormalise(c, Y, tmp, U, EK_F32));
+      Ub = ws_ptr<bf16_t>(c, c.pl.off_ub);
+      LORACT_TRY(launch_convert(c.s, U, EK_F32, Ub, EK_BF16, m * l));
+    }
+    return project(c, Ub, EK_BF16, V, f_ek);
+  }
+  // fp32 input: keep Q in float64 for the projection, hand out fp32 factors
+  LORACT_TRY(orthonormalise(c, Y, tmp, Y, EK_F64));
+  LORACT_TRY(launch_convert(c.s, Y, EK_F64, U, EK_F32, m * l));
+  return project(c, Y, EK_F64, V, EK_F32);
+}
+
+// t rounds of [QR; Y = X (X^T Q)] (Algorithm 1, steps 3-6).  Only Y is orthonormalised.
+static int power_iterations(const Ctx& c, void* Y, void* tmp) {
+  const int l = c.pl.l;
+  for (int it = 0; it < c.p->t; ++it) {
+    void* Zt = c.ws + c.pl.off_zt;
+    if (c.pl.bf16_path) {
+      bf16_t* Qb = ws_ptr<bf16_t>(c, c.pl.off_ub);
+      LORACT_TRY(orthonormalise(c, Y, tmp, Qb, EK_BF16));
+      LORACT_TRY(project(c, Qb, EK_BF16, Zt, EK_BF16));
+    } else {
+      LORACT_TRY(orthonormalise(c, Y, tmp, Y, EK_F64));
+      LORACT_TRY(project(c, Y, EK_F64, Zt, EK_F64));
+    }
+    LORACT_TRY(sketch(c, Zt, c.p->n, nullptr, Y));
+  }
+  (void)l;
+  return LORACT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// C ABI.
+
+extern "C" {
+
+const char* loract_version(void) { return "loract-gfx950 0.1"; }
+
+const char* loract_strerror(int code) {
+  switch (code) {
+    case LORACT_OK: return "ok";
+    case LORACT_ERR_INVALID_ARG: return "invalid argument";
+    case LORACT_ERR_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case LORACT_ERR_UNSUPPORTED: return "unsupported configuration";
+    case LORACT_ERR_NOT_IMPLEMENTED: return "not implemented";
+    case LORACT_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+
+const char* loract_last_hip_error(void) { return g_host.last_hip_error.c_str(); }
+
+int loract_sample_indices(int64_t m, int32_t l, uint64_t seed, int32_t* idx_host) {
+  return sample_indices_host(m, l, seed, idx_host);
+}
+
+int loract_workspace_bytes(const loract_params* p, size_t* bytes) {
+  if (!bytes) return LORACT_ERR_INVALID_ARG;
+  Plan pl;
+  // the RSVD layout is a superset of the compress layout, so one size serves both calls
+  loract_params q;
+  if (!p) return LORACT_ERR_INVALID_ARG;
+  q = *p;
+  int rc = make_plan(&q, true, &pl);
+  if (rc != LORACT_OK) return rc;
+  *bytes = pl.total;
+  return LORACT_OK;
+}
+
+int loract_compress(const void* X_dev, const loract_params* p, const int32_t* idx_host,
+                    void* U_dev, void* V_dev, void* ws_dev, size_t ws_bytes, void* stream,
+                    int32_t* status_dev) {
+  Ctx c;
+  hipStream_t s = (hipStream_t)stream;
+  LORACT_TRY(check_common(X_dev, p, U_dev, V_dev, ws_dev, ws_bytes, false, &c, s, status_dev));
+  const int k = p->k;
+  IdxPack pack;
+  memset(&pack, 0, sizeof(pack));
+  if (idx_host) {
+    for (int i = 0; i < k; ++i) {
+      if (idx_host[i] < 0 || idx_host[i] >= p->m) return LORACT_ERR_INVALID_ARG;
+      if (i > 0 && idx_host[i] <= idx_host[i - 1]) return LORACT_ERR_INVALID_ARG;
+      pack.v[i] = idx_host[i];
+    }
+  } else {
+    LORACT_TRY(sample_indices_host(p->m, k, p->seed, pack.v));
+  }
+  int32_t* idx_dev = ws_ptr<int32_t>(c, c.pl.off_idx);
+  LORACT_LAUNCH("store_indices", s, store_indices_kernel, dim3((k + 255) / 256), dim3(256), 0, pack,
+                k, idx_dev, status_dev);
+  void* Y = c.ws + c.pl.off_a;
+  void* tmp = c.ws + c.pl.off_b;
+  LORACT_TRY(sketch(c, X_dev, p->ldx, idx_dev, Y));       // steps 1-2
+  LORACT_TRY(power_iterations(c, Y, tmp));                // steps 3-6
+  return finish_factors(c, Y, tmp, U_dev, V_dev);         // steps 7-8
+}
+
+int loract_reconstruct(const void* U_dev, const void* V_dev, int64_t m, int64_t n, int32_t k,
+                       int32_t factor_dtype, void* Xhat_dev, int64_t ldxh, int32_t out_dtype,
+                       void* stream) {
+  if (!U_dev || !V_dev || !Xhat_dev || m < 1 || n < 1 || k < 1 || ldxh < n)
+    return LORACT_ERR_INVALID_ARG;
+  if (!dtype_ok(factor_dtype) || !dtype_ok(out_dtype)) return LORACT_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  if (factor_dtype == LORACT_BF16)
+    return launch_gemm_bf16("reconstruct", s, (const bf16_t*)U_dev, k, 1, (const bf16_t*)V_dev, n, 0,
+                            nullptr, m, n, k, Xhat_dev, ldxh,
+                            out_dtype == LORACT_BF16 ? EK_BF16 : EK_F32, 1, nullptr);
+  return launch_gemm_f64("reconstruct_f64", s, U_dev, k, 1, EK_F32, V_dev, n, 0, EK_F32, nullptr, m,
+                         n, k, 1.0, Xhat_dev, ldxh, out_dtype == LORACT_BF16 ? EK_BF16 : EK_F32, 1,
+                         nullptr);
+}
+
+// Workspace of loract_lora_grad: G (m x r, fp32 or bf16), T (k x r, fp32), split partials.
+struct LoraPlan {
+  int t_splits;
+  size_t off_g, off_t, off_dpart, total;
+};
+static int make_lora_plan(int64_t m, int64_t n, int32_t k, int64_t n_out, int32_t r, LoraPlan* lp) {
+  if (m < 1 || n < 1 || k < 1 || n_out < 1 || r < 1 || r > 64) return LORACT_ERR_INVALID_ARG;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+  lp->t_splits = pick_splits(ceil_div64(k, 64), m, 128);
+  lp->off_g = take((size_t)m * r * 4);
+  lp->off_t = take((size_t)k * r * 4);
+  lp->off_dpart = take((size_t)lp->t_splits * k * r * 8);
+  lp->total = off;
+  return LORACT_OK;
+}
+
+int loract_lora_grad_workspace_bytes(int64_t m, int64_t n, int32_t k, int64_t n_out,
+                                     int32_t r_lora, size_t* bytes) {
+  if (!bytes) return LORACT_ERR_INVALID_ARG;
+  LoraPlan lp;
+  LORACT_TRY(make_lora_plan(m, n, k, n_out, r_lora, &lp));
+  *bytes = lp.total;
+  return LORACT_OK;
+}
+
+int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n, int32_t k,
+                     int32_t factor_dtype, const void* dY_dev, int64_t n_out,
+                     const void* Blora_dev, int32_t r_lora, int32_t grad_dtype, float scale,
+                     float* dA_dev, void* ws_dev, size_t ws_bytes, void* stream) {
+  if (!U_dev || !V_dev || !dY_dev || !Blora_dev || !dA_dev) return LORACT_ERR_INVALID_ARG;
+  if (!dtype_ok(factor_dtype) || !dtype_ok(grad_dtype)) return LORACT_ERR_INVALID_ARG;
+  LoraPlan lp;
+  LORACT_TRY(make_lora_plan(m, n, k, n_out, r_lora, &lp));
+  if (!ws_dev || ws_bytes < lp.total) return LORACT_ERR_WORKSPACE_TOO_SMALL;
+  hipStream_t s = (hipStream_t)stream;
+  char* ws = (char*)ws_dev;
+  float* G = (float*)(ws + lp.off_g);
+  float* T = (float*)(ws + lp.off_t);
+  double* dpart = (double*)(ws + lp.off_dpart);
+  const int f_ek = factor_dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
+  // G = dY B_lora^T  (m x r): the only pass over the large operand
+  if (grad_dtype == LORACT_BF16)
+    LORACT_TRY(launch_gemm_bf16("lora_dyb", s, (const bf16_t*)dY_dev, n_out, 1,
+                                (const bf16_t*)Blora_dev, n_out, 1, nullptr, m, r_lora, n_out, G,
+                                r_lora, EK_F32, 1, nullptr));
+  else
+    LORACT_TRY(launch_gemm_f64("lora_dyb_f64", s, dY_dev, n_out, 1, EK_F32, Blora_dev, n_out, 1,
+                               EK_F32, nullptr, m, r_lora, n_out, 1.0, G, r_lora, EK_F32, 1, nullptr));
+  // T = U^T G  (k x r)
+  LORACT_TRY(launch_gemm_f64("lora_utg", s, U_dev, k, 0, f_ek, G, r_lora, 0, EK_F32, nullptr, k,
+                             r_lora, m, 1.0, T, r_lora, EK_F32, lp.t_splits, dpart));
+  // dA = V^T T * scale  (n x r)
+  return launch_gemm_f64("lora_vtt", s, V_dev, n, 0, f_ek, T, r_lora, 0, EK_F32, nullptr, n, r_lora,
+                         k, (double)scale, dA_dev, r_lora, EK_F32, 1, nullptr);
+}
+
+int loract_gaussian_omega_t(void* omegaT_dev, int32_t l, int64_t n, int32_t dtype, uint64_t seed,
+                            void* stream) {
+  if (!omegaT_dev || l < 1 || n < 1 || !dtype_ok(dtype)) return LORACT_ERR_INVALID_ARG;
+  hipStream_t s = (hipStream_t)stream;
+  const int64_t count = (int64_t)l * n;
+  int blocks = (int)std::min<int64_t>(ceil_div64(count, 256), 4096);
+  LORACT_LAUNCH("gaussian", s, gaussian_kernel, dim3(blocks), dim3(256), 0, omegaT_dev,
+                dtype == LORACT_BF16 ? EK_BF16 : EK_F32, count, seed);
+  return LORACT_OK;
+}
+
+int loract_rsvd(const void* X_dev, const loract_params* p, const void* omegaT_dev, void* U_dev,
+                void* V_dev, void* ws_dev, size_t ws_bytes, void* stream, int32_t* status_dev) {
+  (void)X_dev; (void)p; (void)omegaT_dev; (void)U_dev; (void)V_dev; (void)ws_dev; (void)ws_bytes;
+  (void)stream; (void)status_dev;
+  return LORACT_ERR_NOT_IMPLEMENTED;
+}
+
+int loract_profile_begin(void) {
+  g_prof.recs.clear();
+  g_prof.agg.clear();
+  g_prof.order.clear();
+  g_prof.on = true;
+  return LORACT_OK;
+}
+
+int loract_profile_end(void) {
+  g_prof.on = false;
+  for (auto& r : g_prof.recs) {
+    hipError_t e = hipEventSynchronize(r.stop);
+    if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
+    float ms = 0.0f;
+    e = hipEventElapsedTime(&ms, r.start, r.stop);
+    if (e != hipSuccess) return hip_fail(e, "hipEventElapsedTime");
+    auto it = g_prof.agg.find(r.name);
+    if (it == g_prof.agg.end()) {
+      g_prof.agg[r.name] = std::make_pair((double)ms, (int64_t)1);
+      g_prof.order.push_back(r.name);
+    } else {
+      it->second.first += ms;
+      it->second.second += 1;
+    }
+    g_prof.pool.push_back(r.start);
+    g_prof.pool.push_back(r.stop);
+  }
+  g_prof.recs.clear();
+  return LORACT_OK;
+}
+
+int loract_profile_count(void) { return (int)g_prof.order.size(); }
+
+int loract_profile_get(int i, char* name_buf, int name_buf_len, double* total_ms,
+                       int64_t* launches) {
+  if (i < 0 || i >= (int)g_prof.order.size() || !name_buf || name_buf_len < 1)
+    return LORACT_ERR_INVALID_ARG;
+  const std::string& nm = g_prof.order[i];
+  strncpy(name_buf, nm.c_str(), (size_t)name_buf_len - 1);
+  name_buf[name_buf_len - 1] = 0;
+  auto& a = g_prof.agg[nm];
+  if (total_ms) *total_ms = a.first;
+  if (launches) *launches = a.second;
+  return LORACT_OK;
+}
+
+}  // extern "C"
