@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the LoRAct hot path on one MI355X.
+
+One "step" = one pass of the whole hot path over one activation site resident in HBM:
+loract_compress (sample, sketch, orthonormalise, project) + loract_reconstruct +
+loract_lora_grad, on the LLaMA-7B-shaped pre-norm activation (8192 x 4096 bf16, rank 128,
+LoRA rank 16, dY 8192 x 4096).  Inputs are seeded synthetic stand-ins (workloads/synth.py).
+
+Prints ONE JSON line: metric/value = activation GB/s through compress + reconstruct (+ the LoRA
+gradient, which is inside the step), plus
+  roofline     the dominant kernel's algorithmic HBM bytes per launch / its mean duration,
+               measured with HIP events on the library's stream inside this run;
+  cpu_baseline the fp64 numpy oracle timed on this machine's host cores on the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
+FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X published fp64 vector rate
+
+
+def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: int):
+    """(bound, amount per launch, unit) for a kernel name: algorithmic HBM bytes for the
+    streaming kernels, flops for the float64 small-matrix kernels."""
+    fb = b                                      # factor bytes per element (= input dtype here)
+    table = {
+        # reads X once and the k sampled rows, writes Y (fp32)
+        "sketch": ("hbm", m * n * b + k * n * b + m * k * 4),
+        # reads X once and U, writes V
+        "project": ("hbm", m * n * b + m * k * fb + k * n * fb),
+        "project_fused": ("hbm", m * n * b + m * k * 4 + m * k * fb + k * n * 4),
+        # writes Xhat, reads U and V
+        "reconstruct": ("hbm", m * n * b + (m + n) * k * fb),
+        # reads dY once and B_lora, writes G (fp32)
+        "lora_dyb": ("hbm", m * n_out * b + r * n_out * b + m * r * 4),
+    }
+    if name in table:
+        bound, amount = table[name]
+        return bound, float(amount), "GB/s"
+    flops = {
+        "gram": 2.0 * m * k * k,
+        "apply_rinv": 2.0 * m * k * k,
+        "chol_inverse": 2.0 * k ** 3 / 3.0,
+        "lora_utg": 2.0 * m * k * r,
+        "lora_vtt": 2.0 * n * k * r,
+    }
+    if name in flops:
+        return "alu", flops[name], "TFLOP/s"
+    return "hbm", 0.0, "GB/s"
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (each GPU compresses "
+              "its own micro-batch independently); run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import paper_2509_23472_amd as L
+    from workloads import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+
+    if args.workload == "c3":
+        w = synth.c3_llama()
+    else:
+        w = synth.FULL_SIZE[args.workload]()
+    m, n, k = w.m, w.n, w.k
+    b = 2
+    rng = np.random.default_rng(123)
+    dy_h = w.extras.get("dY")
+    bl_h = w.extras.get("B_lora")
+    if dy_h is None:       # the LoRA operands are part of every step; other sites reuse the recipe
+        r_l = 16
+        dy_h = synth.round_to_bf16(rng.standard_normal((m, n)).astype(np.float32))
+        bl_h = synth.round_to_bf16((rng.standard_normal((r_l, n)) / 4.0).astype(np.float32))
+    r_l, n_out = bl_h.shape[0], dy_h.shape[1]
+
+    def up(a):
+        return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
+
+    x, dy, bl = up(w.x), up(dy_h), up(bl_h)
+    u = torch.empty((m, k), dtype=torch.bfloat16, device="cuda")
+    v = torch.empty((k, n), dtype=torch.bfloat16, device="cuda")
+    xhat = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    ga = torch.empty((n, r_l), dtype=torch.float32, device="cuda")
+
+    def compress():
+        L.loract_compress(x, k, seed=w.seed, out=(u, v))
+
+    def reconstruct():
+        L.loract_reconstruct(u, v, out=xhat)
+
+    def lora():
+        L.loract_lora_grad(u, v, dy, bl, scale=1.0, out=ga)
+
+    def step():
+        compress()
+        reconstruct()
+        lora()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    x_bytes = m * n * b
+
+    # per-phase times (separate region, events on the stream the library launches on)
+    def timed(fn):
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / args.steps     # microseconds
+
+    us_c, us_r, us_l = timed(compress), timed(reconstruct), timed(lora)
+
+    # per-kernel times: HIP events recorded by the library around each of its launches
+    L.loract_profile_begin()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    prof = L.loract_profile_end()
+    kernels = {}
+    for name, (ms, cnt) in prof.items():
+        bound, amount, unit = algorithmic_cost(name, m, n, k, b, n_out, r_l)
+        avg_us = ms * 1e3 / cnt
+        kernels[name] = {"avg_us": round(avg_us, 2), "launches_per_step": cnt / args.steps,
+                         "share": 0.0, "bound": bound,
+                         "achieved": round(amount / (avg_us * 1e-6) / (1e9 if unit == "GB/s" else 1e12), 2)
+                         if amount else None, "unit": unit}
+    total_ms = sum(ms for ms, _ in prof.values())
+    for name, (ms, cnt) in prof.items():
+        kernels[name]["share"] = round(ms / total_ms, 3)
+    dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
+    d_bound, d_amount, d_unit = algorithmic_cost(dom, m, n, k, b, n_out, r_l)
+    d_avg_s = prof[dom][0] * 1e-3 / prof[dom][1]
+    if d_unit == "GB/s":
+        achieved, peak = d_amount / d_avg_s / 1e9, HBM_PEAK_GBS
+    else:
+        achieved, peak = d_amount / d_avg_s / 1e12, FP64_VECTOR_PEAK_TFLOPS
+    traffic = None
+    if os.path.exists(args.traffic_json):
+        try:
+            traffic = json.load(open(args.traffic_json)).get(args.workload, {}).get(dom)
+        except Exception:
+            traffic = None
+    roofline = {"kernel": dom, "bound": d_bound, "achieved": round(achieved, 2), "peak": peak,
+                "unit": d_unit, "frac": round(achieved / peak, 4), "traffic": traffic,
+                "avg_us": round(d_avg_s * 1e6, 2), "algorithmic_per_launch": d_amount}
+
+    # accuracy of the timed outputs (cheap GPU-side figure; full parity lives in tests/)
+    err = float((torch.linalg.norm(xhat.float() - x.float()) / torch.linalg.norm(x.float())).item())
+
+    out = {
+        "metric": "activation GB/s compressed+reconstructed",
+        "value": round(x_bytes / (ms_per_step * 1e-3) / 1e9, 2),
+        "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "%s: %dx%d bf16, rank %d, LoRA rank %d, dY %dx%d; step = compress + "
+                               "reconstruct + lora_grad" % (args.workload, m, n, k, r_l, m, n_out)},
+        "phases_us": {"compress": round(us_c, 1), "reconstruct": round(us_r, 1), "lora_grad": round(us_l, 1)},
+        "gbps": {"compress": round(x_bytes / us_c / 1e3, 1), "reconstruct": round(x_bytes / us_r / 1e3, 1),
+                 "round_trip": round(x_bytes / (us_c + us_r) / 1e3, 1)},
+        "hbm_frac_two_pass": round((2 * x_bytes + k * n * b + 2 * m * k * 4 + 2 * (m + n) * k * b + x_bytes)
+                                   / ((us_c + us_r) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+        "rel_fro_err": round(err, 6),
+        "roofline": roofline,
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import loract_oracle as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+        except Exception:
+            cores = os.cpu_count() or 1
+        x64 = w.x.astype(np.float64)
+        reps, t_start = 0, time.perf_counter()
+        while True:
+            uo, vo = orc.decompose(x64, k, seed=w.seed)
+            xo = orc.reconstruct(uo, vo)
+            orc.lora_grad(uo, vo, dy_h, bl_h, 1.0)
+            reps += 1
+            elapsed = time.perf_counter() - t_start
+            if elapsed >= 10.0 or reps >= 200:
+                break
+        out["cpu_baseline"] = {"value": round(x_bytes / (elapsed / reps) / 1e9, 4), "unit": "GB/s",
+                               "cores": int(cores), "kind": "oracle",
+                               "sample": "%d full steps of the same %s workload (fp64 numpy oracle, "
+                                         "%.1f s)" % (reps, args.workload, elapsed)}
+        out["parity_vs_oracle"] = round(orc.rel_fro(xhat.float().cpu().numpy(), xo), 6)
+
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

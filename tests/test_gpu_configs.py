@@ -1,0 +1,75 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration
+bench.py times.  The fp64 oracle finishes each of these in seconds, so the whole reconstruction
+is compared (not a sample).  Inputs are the seeded synthetic stand-ins for the paper's
+ViT-B/16 and LLaMA2-7B activations (workloads/synth.py).
+"""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import loract_oracle as orc
+from workloads import synth
+
+from gpu_util import TOL_PARITY, check_compress_parity, to_device, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def _compress_reconstruct(w):
+    import paper_2509_23472_amd as L
+    print("case", w.name, "bytes", w.nbytes, flush=True)
+    x = to_device(w.x, w.dtype)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    u, v = L.loract_compress(x, w.k, seed=w.seed, status=status)
+    xhat = L.loract_reconstruct(u, v)
+    torch.cuda.synchronize()
+    return L, x, u, v, xhat, int(status.item())
+
+
+@pytest.mark.parametrize("name", ["c2a", "c2b"])
+def test_c2_vit_sites(name):
+    w = synth.FULL_SIZE[name]()
+    L, x, u, v, xhat, status = _compress_reconstruct(w)
+    res = check_compress_parity(w, u, v, xhat, strict_ortho=True)
+    print(name, res, "status", status)
+    assert status == 0
+
+
+def test_c3_llama_prenorm_site_with_lora_grad():
+    w = synth.c3_llama()
+    L, x, u, v, xhat, status = _compress_reconstruct(w)
+    t0 = time.time()
+    uo, vo = orc.decompose(w.x.astype(np.float64), w.k, seed=w.seed)
+    print("oracle decompose %.1fs" % (time.time() - t0), flush=True)
+    res = check_compress_parity(w, u, v, xhat, oracle_factors=(uo, vo), strict_ortho=True)
+    print("c3", res, "status", status)
+    assert status == 0
+    dy, b = w.extras["dY"], w.extras["B_lora"]
+    g = L.loract_lora_grad(u, v, to_device(dy, "bf16"), to_device(b, "bf16"), scale=w.extras["scale"])
+    torch.cuda.synchronize()
+    ref = orc.lora_grad(uo, vo, dy, b, w.extras["scale"])
+    err = orc.rel_fro(to_host(g), ref)
+    print("c3 lora_grad parity", err)
+    assert g.shape == (w.n, w.extras["r_lora"])
+    assert err <= TOL_PARITY["bf16"]
+
+
+def test_c4_llama_mlp_site():
+    w = synth.c4_mlp()
+    L, x, u, v, xhat, status = _compress_reconstruct(w)
+    res = check_compress_parity(w, u, v, xhat, strict_ortho=True)
+    print("c4", res, "status", status)
+    assert status == 0
+
+
+def test_c5_long_context_site():
+    # one 65536 x 4096 site of the long-context stream (layer 0, site 0), k = 256
+    w = synth.c5_long_context_site(0, 0)
+    L, x, u, v, xhat, status = _compress_reconstruct(w)
+    t0 = time.time()
+    uo, vo = orc.decompose(w.x.astype(np.float64), w.k, seed=w.seed)
+    print("oracle decompose %.1fs" % (time.time() - t0), flush=True)
+    res = check_compress_parity(w, u, v, xhat, oracle_factors=(uo, vo), strict_ortho=True)
+    print("c5", res, "status", status)
