@@ -26,6 +26,7 @@ struct GemmBf16Args {
   int64_t ldc;
   float* Cpart;           // [splits][M][N] partial sums when gridDim.z > 1
   int64_t M, N, K;
+  int64_t n_pad;          // columns N..n_pad-1 of C are written as zero (unsplit launches only)
   int64_t k_per_split;    // multiple of 32
   int a_kc, b_kc;         // 1 = K-contiguous, 0 = K-strided
   int a_vec, b_vec;       // 16-byte vector loads are legal for this operand
@@ -107,8 +108,19 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(GemmBf16Args g) {
   // 32x32 accumulator layout: register r of lane l holds
   // row 8*(r/4) + 4*(l/32) + r%4, column l%32 of the wave's sub-tile.
   const int64_t col = col0 + wn * 32 + (lane & 31);
-  if (col >= g.N) return;
   const bool split = gridDim.z > 1;
+  if (col >= g.N) {
+    if (!split && col < g.n_pad) {
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = row0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row >= g.M) continue;
+        if (g.out_kind == EK_F32) ((float*)g.C)[row * g.ldc + col] = 0.0f;
+        else ((bf16_t*)g.C)[row * g.ldc + col] = (bf16_t)0.0f;
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < 16; ++r) {
     const int64_t row = row0 + wm * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -146,9 +158,11 @@ static inline bool gb_vec_ok(const void* p, int64_t ld) {
 static int launch_gemm_bf16(const char* name, hipStream_t stream, const bf16_t* A, int64_t lda,
                             int a_kc, const bf16_t* B, int64_t ldb, int b_kc,
                             const int32_t* b_rows, int64_t M, int64_t N, int64_t K, void* C,
-                            int64_t ldc, int out_kind, int splits, float* Cpart) {
+                            int64_t ldc, int out_kind, int splits, float* Cpart,
+                            int64_t n_pad = 0) {
   if (M <= 0 || N <= 0 || K <= 0) return LORACT_OK;
   GemmBf16Args g;
+  g.n_pad = n_pad;
   g.A = A; g.lda = lda; g.B = B; g.ldb = ldb; g.b_rows = b_rows;
   g.C = C; g.ldc = ldc; g.Cpart = Cpart; g.M = M; g.N = N; g.K = K;
   g.a_kc = a_kc; g.b_kc = b_kc;
@@ -158,7 +172,8 @@ static int launch_gemm_bf16(const char* name, hipStream_t stream, const bf16_t* 
   int64_t kps = ceil_div64(ceil_div64(K, splits), GB_BK) * GB_BK;
   splits = (int)ceil_div64(K, kps);
   g.k_per_split = kps;
-  dim3 grid((unsigned)ceil_div64(M, GB_BM), (unsigned)ceil_div64(N, GB_BN), (unsigned)splits);
+  dim3 grid((unsigned)ceil_div64(M, GB_BM), (unsigned)ceil_div64(std::max(N, n_pad), GB_BN),
+            (unsigned)splits);
   if (grid.y > 65535 || grid.z > 65535) return LORACT_ERR_UNSUPPORTED;
   LORACT_LAUNCH(name, stream, gemm_bf16_kernel, grid, dim3(256), 0, g);
   if (splits > 1) {

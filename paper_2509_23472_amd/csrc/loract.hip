@@ -3,6 +3,8 @@
 #include "gemm_bf16.h"
 #include "gemm_f64.h"
 #include "chol.h"
+#include "ortho_f64.h"
+#include "stream_bf16.h"
 
 #include <algorithm>
 #include <cmath>
@@ -83,9 +85,11 @@ static int sample_indices_host(int64_t m, int32_t l, uint64_t seed, int32_t* out
 struct Plan {
   int bf16_path;
   int l;                 // sketch columns
+  int kp;                // l rounded up to a multiple of 16 (column count of the fp32 work buffers)
   int gram_splits, proj_splits;
   size_t off_idx, off_a, off_b, off_ub, off_g, off_rinv, off_dpart, off_fpart, off_zt;
-  size_t off_bmat, off_eig, off_omega;
+  size_t off_bmat, off_eig, off_omega, off_dinv;
+  int sketch_splits;
   size_t total;
 };
 
@@ -119,7 +123,8 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->l = l;
   pl->bf16_path = (p->x_dtype == LORACT_BF16);
   const int64_t m = p->m, n = p->n;
-  const size_t ybytes = (size_t)m * l * (pl->bf16_path ? 4 : 8);
+  pl->kp = (l + 15) / 16 * 16;
+  const size_t ybytes = pl->bf16_path ? (size_t)m * pl->kp * 4 : (size_t)m * l * 8;
   const int64_t lt = ceil_div64(l, 64);
   pl->gram_splits = pick_splits(lt * lt, m, 256);
   pl->proj_splits = pick_splits(lt * ceil_div64(n, 64), m, 256);
@@ -129,12 +134,22 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_a = take(ybytes);
   pl->off_b = take(ybytes);
   pl->off_ub = take(pl->bf16_path ? (size_t)m * l * 2 : 0);
-  pl->off_g = take((size_t)l * l * 8);
+  pl->off_g = take((size_t)pl->kp * pl->kp * 8);
   pl->off_rinv = take((size_t)l * l * 8);
+  pl->off_dinv = take((size_t)pl->kp * 16 * 8);
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
+  if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
   pl->off_dpart = take(dpart);
-  pl->off_fpart = take(pl->bf16_path ? (size_t)pl->proj_splits * l * n * 4 : 0);
+  size_t fpart = 0;
+  pl->sketch_splits = 1;
+  if (pl->bf16_path) {
+    pl->sketch_splits = sketch_splits_for(m, n, pl->kp);
+    pl->proj_splits = std::max(pl->proj_splits, project_splits_for(m, n, l));
+    fpart = std::max((size_t)pl->proj_splits * l * n * 4,
+                     pl->sketch_splits > 1 ? (size_t)pl->sketch_splits * m * pl->kp * 4 : (size_t)0);
+  }
+  pl->off_fpart = take(fpart);
   const bool need_zt = p->t > 0 || rsvd;
   pl->off_zt = take(need_zt ? (size_t)l * n * (pl->bf16_path ? 2 : 8) : 0);
   pl->off_bmat = take(rsvd && l > p->k ? (size_t)l * n * (pl->bf16_path ? 4 : 8) : 0);
@@ -166,9 +181,18 @@ static T* ws_ptr(const Ctx& c, size_t off) { return (T*)(c.ws + off); }
 static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows, void* Y) {
   const int64_t m = c.p->m, n = c.p->n;
   const int l = c.pl.l;
-  if (c.pl.bf16_path)
-    return launch_gemm_bf16("sketch", c.s, (const bf16_t*)c.X, c.p->ldx, 1, (const bf16_t*)Bt, ldb,
-                            1, rows, m, l, n, Y, l, EK_F32, 1, nullptr);
+  if (c.pl.bf16_path) {
+    if (sb_aligned(c.X, c.p->ldx) && sb_aligned(Bt, ldb) && n % 8 == 0) {
+      SketchArgs a;
+      a.X = (const bf16_t*)c.X; a.ldx = c.p->ldx; a.m = m; a.n = n;
+      a.B = (const bf16_t*)Bt; a.ldb = ldb; a.b_rows = rows; a.l = l; a.kp = c.pl.kp;
+      a.Y = (float*)Y; a.part = ws_ptr<float>(c, c.pl.off_fpart); a.splits = c.pl.sketch_splits;
+      a.k_per_split = 0;
+      return launch_sketch_mfma(c.s, a);
+    }
+    return launch_gemm_bf16("sketch_generic", c.s, (const bf16_t*)c.X, c.p->ldx, 1, (const bf16_t*)Bt,
+                            ldb, 1, rows, m, l, n, Y, c.pl.kp, EK_F32, 1, nullptr, c.pl.kp);
+  }
   return launch_gemm_f64("sketch_f64", c.s, c.X, c.p->ldx, 1, EK_F32, Bt, ldb, 1,
                          rows ? EK_F32 : EK_F64, rows, m, l, n, 1.0, Y, l, EK_F64, 1, nullptr);
 }
@@ -199,14 +223,49 @@ static int orthonormalise(const Ctx& c, void* Y, void* tmp, void* Qout, int q_ek
   return LORACT_OK;
 }
 
+// bf16 path: the same two rounds on the matrix cores.  Y is m x kp float32 (zero padded
+// columns); round 1 factors the shifted Gram matrix and writes Q1 (float32) into tmp, round 2
+// writes the orthonormal factor as `Q` (element kind q_ek, k columns, leading dimension k) and,
+// if Qb is given, a bf16 copy with the same shape.
+static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q, int q_ek,
+                               bf16_t* Qb) {
+  const int64_t m = c.p->m;
+  const int l = c.pl.l, kp = c.pl.kp;
+  double* G = ws_ptr<double>(c, c.pl.off_g);
+  double* Dinv = ws_ptr<double>(c, c.pl.off_dinv);
+  double* part = ws_ptr<double>(c, c.pl.off_dpart);
+  const double shift_rel = 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16;
+  TrsmArgs t;
+  t.L = G; t.Dinv = Dinv; t.m = m; t.kp = kp; t.k = l;
+  // round 1
+  LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, part, G));
+  LORACT_TRY(launch_chol_blocked(c.s, G, Dinv, l, kp, shift_rel, c.status));
+  t.Y = Y; t.ldy = kp; t.Q = tmp; t.ldq = kp; t.out_ek = EK_F32; t.out_cols = kp;
+  t.Qb = nullptr; t.ldqb = 0;
+  LORACT_TRY(launch_trsm_apply(c.s, t));
+  // round 2
+  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, part, G));
+  LORACT_TRY(launch_chol_blocked(c.s, G, Dinv, l, kp, 0.0, c.status));
+  t.Y = tmp; t.Q = Q; t.ldq = l; t.out_ek = q_ek; t.out_cols = l; t.Qb = Qb; t.ldqb = l;
+  return launch_trsm_apply(c.s, t);
+}
+
 // Bt (l x n) = Q^T X: step 8 of Algorithm 1 (and the first half of step 5).
 static int project(const Ctx& c, const void* Q, int q_ek, void* Bt, int out_ek) {
   const int64_t m = c.p->m, n = c.p->n;
   const int l = c.pl.l;
-  if (c.pl.bf16_path)
-    return launch_gemm_bf16("project", c.s, (const bf16_t*)Q, l, 0, (const bf16_t*)c.X, c.p->ldx, 0,
-                            nullptr, l, n, m, Bt, n, out_ek, c.pl.proj_splits,
+  if (c.pl.bf16_path) {
+    if (sb_aligned(c.X, c.p->ldx) && sb_aligned(Q, l) && sb_aligned(Bt, n)) {
+      ProjectArgs a;
+      a.Q = (const bf16_t*)Q; a.ldq = l; a.X = (const bf16_t*)c.X; a.ldx = c.p->ldx; a.m = m; a.n = n;
+      a.l = l; a.V = Bt; a.out_ek = out_ek; a.part = ws_ptr<float>(c, c.pl.off_fpart);
+      a.splits = project_splits_for(m, n, l); a.rows_per_split = 0;
+      return launch_project_mfma(c.s, a);
+    }
+    return launch_gemm_bf16("project_generic", c.s, (const bf16_t*)Q, l, 0, (const bf16_t*)c.X,
+                            c.p->ldx, 0, nullptr, l, n, m, Bt, n, out_ek, c.pl.proj_splits,
                             ws_ptr<float>(c, c.pl.off_fpart));
+  }
   return launch_gemm_f64("project_f64", c.s, Q, l, 0, q_ek, c.X, c.p->ldx, 0, EK_F32, nullptr, l, n,
                          m, 1.0, Bt, n, out_ek, c.pl.proj_splits, ws_ptr<double>(c, c.pl.off_dpart));
 }
@@ -236,11 +295,10 @@ static int finish_factors(const Ctx& c, void* Y, void* tmp, void* U, void* V) {
   if (c.pl.bf16_path) {
     bf16_t* Ub = (bf16_t*)U;
     if (f_ek == EK_BF16) {
-      LORACT_TRY(orthonormalise(c, Y, tmp, U, EK_BF16));
+      LORACT_TRY(orthonormalise_mfma(c, (const float*)Y, (float*)tmp, U, EK_BF16, nullptr));
     } else {
-      LORACT_TRY(orthonormalise(c, Y, tmp, U, EK_F32));
       Ub = ws_ptr<bf16_t>(c, c.pl.off_ub);
-      LORACT_TRY(launch_convert(c.s, U, EK_F32, Ub, EK_BF16, m * l));
+      LORACT_TRY(orthonormalise_mfma(c, (const float*)Y, (float*)tmp, U, EK_F32, Ub));
     }
     return project(c, Ub, EK_BF16, V, f_ek);
   }
@@ -257,7 +315,7 @@ static int power_iterations(const Ctx& c, void* Y, void* tmp) {
     void* Zt = c.ws + c.pl.off_zt;
     if (c.pl.bf16_path) {
       bf16_t* Qb = ws_ptr<bf16_t>(c, c.pl.off_ub);
-      LORACT_TRY(orthonormalise(c, Y, tmp, Qb, EK_BF16));
+      LORACT_TRY(orthonormalise_mfma(c, (const float*)Y, (float*)tmp, Qb, EK_BF16, nullptr));
       LORACT_TRY(project(c, Qb, EK_BF16, Zt, EK_BF16));
     } else {
       LORACT_TRY(orthonormalise(c, Y, tmp, Y, EK_F64));
@@ -342,8 +400,15 @@ int loract_reconstruct(const void* U_dev, const void* V_dev, int64_t m, int64_t 
     return LORACT_ERR_INVALID_ARG;
   if (!dtype_ok(factor_dtype) || !dtype_ok(out_dtype)) return LORACT_ERR_INVALID_ARG;
   hipStream_t s = (hipStream_t)stream;
+  if (factor_dtype == LORACT_BF16 && out_dtype == LORACT_BF16 && k <= LORACT_MAX_RANK &&
+      sb_aligned(U_dev, k) && sb_aligned(V_dev, n) && sb_aligned(Xhat_dev, ldxh)) {
+    ReconArgs a;
+    a.U = (const bf16_t*)U_dev; a.V = (const bf16_t*)V_dev; a.m = m; a.n = n; a.k = k;
+    a.Xhat = (bf16_t*)Xhat_dev; a.ldxh = ldxh; a.row_tiles = 0;
+    return launch_reconstruct_mfma(s, a);
+  }
   if (factor_dtype == LORACT_BF16)
-    return launch_gemm_bf16("reconstruct", s, (const bf16_t*)U_dev, k, 1, (const bf16_t*)V_dev, n, 0,
+    return launch_gemm_bf16("reconstruct_generic", s, (const bf16_t*)U_dev, k, 1, (const bf16_t*)V_dev, n, 0,
                             nullptr, m, n, k, Xhat_dev, ldxh,
                             out_dtype == LORACT_BF16 ? EK_BF16 : EK_F32, 1, nullptr);
   return launch_gemm_f64("reconstruct_f64", s, U_dev, k, 1, EK_F32, V_dev, n, 0, EK_F32, nullptr, m,

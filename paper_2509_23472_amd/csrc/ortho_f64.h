@@ -1,0 +1,508 @@
+// Tall-skinny orthonormalisation kernels of the bf16 path: Gram matrix, Cholesky factor and
+// triangular solve, all accumulated in float64 on the gfx950 matrix cores
+// (v_mfma_f64_16x16x4_f64) without LDS staging of the operands.
+//
+// Layout conventions used below (verified on the device):
+//   A operand (16 x 4):  lane l holds A[m = l % 16][kk = l / 16]
+//   B operand (4 x 16):  lane l holds B[kk = l / 16][n = l % 16]
+//   C/D      (16 x 16):  register r of lane l holds D[m = 4 r + l / 16][n = l % 16]
+// so an accumulator can be fed back as the B operand of a later product whose contraction
+// index is the accumulator's row index: slice r (kk = 4 r .. 4 r + 3) is register r.
+//
+// The sketch Y and the intermediate Q1 are stored as m x kp float32 with kp = k rounded up to a
+// multiple of 16; columns k..kp-1 are zero.  The Gram matrix / Cholesky factor is kp x kp.
+#pragma once
+#include "common.h"
+
+#define OF_NB 16
+
+// Phase timestamps for development harnesses; compiled out in the library build.
+#ifdef OF_SKIP
+__device__ int of_skip_mask;     // development harness only: bit 0 skips panels, bit 1 trailing updates
+#define OF_SKIPPED(bit) (of_skip_mask & (bit))
+#else
+#define OF_SKIPPED(bit) false
+#endif
+#ifdef OF_TIMING
+__device__ long long of_stamps[64];
+#define OF_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) of_stamps[i] = wall_clock64(); } while (0)
+#else
+#define OF_STAMP(i) do { } while (0)
+#endif
+
+__device__ inline f64x4 mfma_f64(double a, double b, f64x4 c) {
+  return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Gram matrix G = Y^T Y (lower 64 x 64 blocks only), rows split into chunks; one workgroup per
+// (chunk, block), each of its 4 waves owning a 32 x 32 sub-block (2 x 2 MFMA tiles).
+// part[(chunk * nblocks + block) * 4096 + i * 64 + j] holds the chunk's contribution.
+
+struct GramArgs {
+  const float* Y;
+  int64_t ldy;
+  int64_t m;
+  int kp;
+  int rows_per_chunk;   // multiple of 4
+  int nb64;             // number of 64-wide block rows = ceil(kp / 64)
+  double* part;
+};
+
+__device__ inline void gram_block_of(int b, int* bi, int* bj) {
+  int i = 0;
+  while ((i + 1) * (i + 2) / 2 <= b) ++i;
+  *bi = i;
+  *bj = b - i * (i + 1) / 2;
+}
+
+__global__ __launch_bounds__(256) void gram_mfma_kernel(GramArgs g) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  int bi, bj;
+  gram_block_of(blockIdx.y, &bi, &bj);
+  const int wi = wave >> 1, wj = wave & 1;
+  const int ca = bi * 64 + wi * 32;   // first Gram row (a column of Y) of this wave's sub-block
+  const int cb = bj * 64 + wj * 32;
+  const int64_t r_begin = (int64_t)blockIdx.x * g.rows_per_chunk;
+  const int64_t r_end = (r_begin + g.rows_per_chunk < g.m) ? r_begin + g.rows_per_chunk : g.m;
+  const int lc = lane & 15, lr = lane >> 4;
+
+  f64x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = (f64x4){0.0, 0.0, 0.0, 0.0};
+
+  const bool a_ok0 = ca + lc < g.kp, a_ok1 = ca + 16 + lc < g.kp;
+  const bool b_ok0 = cb + lc < g.kp, b_ok1 = cb + 16 + lc < g.kp;
+  // 16 rows per trip: all 16 loads are issued before the 16 matrix instructions consume them
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += 16) {
+    float fa0[4], fa1[4], fb0[4], fb1[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int64_t row = r0 + 4 * u + lr;
+      const bool rok = row < r_end;
+      const float* yr = g.Y + (rok ? row : r_begin) * g.ldy;
+      fa0[u] = (rok && a_ok0) ? yr[ca + lc] : 0.0f;
+      fa1[u] = (rok && a_ok1) ? yr[ca + 16 + lc] : 0.0f;
+      fb0[u] = (rok && b_ok0) ? yr[cb + lc] : 0.0f;
+      fb1[u] = (rok && b_ok1) ? yr[cb + 16 + lc] : 0.0f;
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const double a0 = (double)fa0[u], a1 = (double)fa1[u];
+      const double b0 = (double)fb0[u], b1 = (double)fb1[u];
+      acc[0][0] = mfma_f64(a0, b0, acc[0][0]);
+      acc[0][1] = mfma_f64(a0, b1, acc[0][1]);
+      acc[1][0] = mfma_f64(a1, b0, acc[1][0]);
+      acc[1][1] = mfma_f64(a1, b1, acc[1][1]);
+    }
+  }
+  double* out = g.part + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * 4096;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+        out[(wi * 32 + i * 16 + 4 * r + lr) * 64 + wj * 32 + j * 16 + lc] = acc[i][j][r];
+}
+
+// G[i][j] (lower triangle, kp x kp) = sum over chunks, ascending.  One thread per element.
+__global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, int chunks,
+                                                          int nblocks, int kp, double* G) {
+  const int b = blockIdx.y;
+  int bi, bj;
+  gram_block_of(b, &bi, &bj);
+  const int e = blockIdx.x * 256 + threadIdx.x;     // gridDim.x = 16
+  const int i = bi * 64 + (e >> 6), j = bj * 64 + (e & 63);
+  if (i >= kp || j >= kp) return;
+  const double* src = part + (int64_t)b * 4096 + e;
+  const int64_t stride = (int64_t)nblocks * 4096;
+  double s = 0.0;
+  int c = 0;
+  for (; c + 8 <= chunks; c += 8) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(c + u) * stride];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += v[u];
+  }
+  for (; c < chunks; ++c) s += src[(int64_t)c * stride];
+  G[(int64_t)i * kp + j] = s;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Blocked Cholesky factorisation G (+ shift) = L L^T of the kp x kp Gram matrix by one workgroup,
+// working in LDS when the matrix fits (kp <= 128) and in global memory otherwise.
+//
+// Per 16-column panel: every wave holds the 16 diagonal-block rows redundantly in lanes 0..15 and
+// up to 48 rows below in lanes 16..63, one row per lane with its 16 panel entries in registers;
+// the 16 pivot steps then need no workgroup barrier, only wave-wide lane reads.  The trailing
+// lower triangle is updated in 4 x 4 register tiles.
+//
+// Outputs: L in the strict lower triangle of G (global), and Dinv[b] = inverse of the b-th
+// 16 x 16 diagonal block of L (row-major, lower triangular), which is what the triangular solve
+// in trsm_apply_kernel consumes.
+//
+// Pivot rule: see chol.h.  Columns k..kp-1 are padding: their reciprocal pivot is whatever the
+// rule gives (zero without a shift) and they never raise the status flag.
+
+__device__ inline double readlane_f64(double v, int src_lane) {
+  union { double d; int i[2]; } u;
+  u.d = v;
+  u.i[0] = __builtin_amdgcn_readlane(u.i[0], src_lane);
+  u.i[1] = __builtin_amdgcn_readlane(u.i[1], src_lane);
+  return u.d;
+}
+
+// 1 / sqrt(x) to float64 accuracy: hardware estimate refined by two Newton steps.
+__device__ inline double rsqrt_f64(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+#pragma unroll
+  for (int it = 0; it < 2; ++it) {
+    const double e = fma(-x * y, y, 1.0);           // 1 - x y^2
+    y = fma(y * fma(0.375, e, 0.5), e, y);          // y (1 + e/2 + 3 e^2 / 8)
+  }
+  return y;
+}
+
+#define CHOL_THREADS 512
+
+template <bool LDS_MODE>
+__global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, double* Dinv, int k,
+                                                                    int kp, double tol,
+                                                                    double shift_rel,
+                                                                    int32_t* status) {
+  extern __shared__ double smem[];
+  // layout: gdiag[kp] | dinv[kp] | misc[8] | Pt[16][kp - 16] | (LDS mode) A[kp][kp + 2]
+  double* gdiag = smem;            // original diagonal
+  double* dinv = smem + kp;        // reciprocal pivots
+  double* misc = smem + 2 * kp;    // [0] = shift
+  const int ptld = kp > OF_NB ? kp - OF_NB : 2;
+  double* Pt = smem + 2 * kp + 8;  // panel below the diagonal block, transposed: Pt[p][row - below]
+  double* Am = LDS_MODE ? (Pt + OF_NB * ptld) : G;
+  const int lda = LDS_MODE ? kp + 2 : kp;
+  __shared__ int deficient;
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  OF_STAMP(0);
+#ifdef OF_TIMING
+  long long t_panel = 0, t_trail = 0, t_mark = 0;
+#endif
+  if (LDS_MODE) {
+    // kp is a multiple of 16: copy whole rows two doubles at a time
+    const int half = kp >> 1;
+#pragma unroll 8
+    for (int e = t; e < kp * half; e += CHOL_THREADS) {
+      const int i = e / half, j2 = e - i * half;
+      const double2 v = *(const double2*)(G + (int64_t)i * kp + 2 * j2);
+      *(double2*)(Am + i * lda + 2 * j2) = v;
+    }
+  }
+  for (int i = t; i < kp; i += CHOL_THREADS) gdiag[i] = G[(int64_t)i * kp + i];
+  if (t == 0) deficient = 0;
+  __syncthreads();
+  OF_STAMP(1);
+  if (wave == 0) {
+    double tr = 0.0;
+    for (int i = lane; i < kp; i += 64) tr += gdiag[i];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) tr += __shfl_xor(tr, off);
+    if (lane == 0) misc[0] = shift_rel * tr;
+  }
+  __syncthreads();
+  const double shift = misc[0];
+  OF_STAMP(2);
+
+  for (int jb = 0; jb < kp; jb += OF_NB) {
+#ifdef OF_TIMING
+    t_mark = wall_clock64();
+#endif
+    const int below = jb + OF_NB;
+    const int nrows_below = kp - below;
+
+    // ---- panel: one row per lane, its 16 panel entries in registers.  Lanes 0..15 of every
+    // wave hold the diagonal block (redundantly), lanes 16..63 hold 48 of the rows below.
+    const int row = (lane < 16) ? (jb + lane) : (below + wave * 48 + lane - 16);
+    const bool row_ok = row < kp;
+    double a[OF_NB];
+    double thr[OF_NB];
+#pragma unroll
+    for (int c = 0; c < OF_NB; ++c) {
+      double v = 0.0;
+      if (row_ok && (lane >= 16 || c <= lane)) v = Am[row * lda + jb + c];
+      if (lane < 16 && c == lane) v += shift;
+      a[c] = v;
+      thr[c] = tol * gdiag[jb + c];
+    }
+    __syncthreads();   // every wave has read the unfactored diagonal block
+    double dval[OF_NB];
+    bool any_bad = false;
+    if (!OF_SKIPPED(1))
+#pragma unroll
+    for (int j = 0; j < OF_NB; ++j) {
+      const double piv = readlane_f64(a[j], j);
+      const bool usable = shift > 0.0 ? (piv > 0.0) : (piv > thr[j]);
+      const double d = usable ? rsqrt_f64(piv) : 0.0;
+      dval[j] = d;
+      any_bad = any_bad || (!usable && jb + j < k);
+      a[j] *= d;
+#pragma unroll
+      for (int c = j + 1; c < OF_NB; ++c) {
+        const double lcj = readlane_f64(a[j], c);
+        a[c] = fma(-a[j], lcj, a[c]);
+      }
+    }
+    if (lane >= 16) {
+      if (row_ok) {
+#pragma unroll
+        for (int c = 0; c < OF_NB; ++c) {
+          Am[row * lda + jb + c] = a[c];
+          Pt[c * ptld + row - below] = a[c];
+        }
+      }
+    } else if (wave == 0) {   // wave 0 owns the diagonal block
+#pragma unroll
+      for (int c = 0; c < OF_NB; ++c)
+        if (c < lane) Am[row * lda + jb + c] = a[c];
+      if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < OF_NB; ++j) dinv[jb + j] = dval[j];
+        if (any_bad) deficient = 1;
+      }
+    }
+    __syncthreads();
+#ifdef OF_TIMING
+    { long long now = wall_clock64(); t_panel += now - t_mark; t_mark = now; }
+#endif
+
+    // ---- trailing update of the lower triangle, 4 x 4 tiles
+    const int nt = nrows_below / 4;
+    const int ntiles = nt * (nt + 1) / 2;
+    for (int e = t; e < ntiles && !OF_SKIPPED(2); e += CHOL_THREADS) {
+      int ti = (int)((sqrtf(8.0f * (float)e + 1.0f) - 1.0f) * 0.5f);
+      while (ti * (ti + 1) / 2 > e) --ti;
+      while ((ti + 1) * (ti + 2) / 2 <= e) ++ti;
+      const int tc = e - ti * (ti + 1) / 2;
+      double acc[4][4];
+#pragma unroll
+      for (int x = 0; x < 4; ++x)
+#pragma unroll
+        for (int y = 0; y < 4; ++y) acc[x][y] = 0.0;
+#pragma unroll 4
+      for (int p = 0; p < OF_NB; ++p) {
+        const double2 pi01 = *(const double2*)(Pt + p * ptld + 4 * ti);
+        const double2 pi23 = *(const double2*)(Pt + p * ptld + 4 * ti + 2);
+        const double2 pc01 = *(const double2*)(Pt + p * ptld + 4 * tc);
+        const double2 pc23 = *(const double2*)(Pt + p * ptld + 4 * tc + 2);
+        const double pi[4] = {pi01.x, pi01.y, pi23.x, pi23.y};
+        const double pc[4] = {pc01.x, pc01.y, pc23.x, pc23.y};
+#pragma unroll
+        for (int x = 0; x < 4; ++x)
+#pragma unroll
+          for (int y = 0; y < 4; ++y) acc[x][y] = fma(pi[x], pc[y], acc[x][y]);
+      }
+      const int i0 = below + 4 * ti, c0 = below + 4 * tc;
+#pragma unroll
+      for (int x = 0; x < 4; ++x) {
+        double* dst = Am + (i0 + x) * lda + c0;
+        double2 v01 = *(double2*)dst, v23 = *(double2*)(dst + 2);
+        v01.x -= acc[x][0]; v01.y -= acc[x][1]; v23.x -= acc[x][2]; v23.y -= acc[x][3];
+        *(double2*)dst = v01;
+        *(double2*)(dst + 2) = v23;
+      }
+    }
+    __syncthreads();
+#ifdef OF_TIMING
+    t_trail += wall_clock64() - t_mark;
+#endif
+  }
+  OF_STAMP(3);
+#ifdef OF_TIMING
+  if (t == 0) { of_stamps[10] = t_panel; of_stamps[11] = t_trail; }
+#endif
+
+  // ---- inverses of the 16 x 16 diagonal blocks, one thread per (block, column)
+  const int nblk = kp / OF_NB;
+  for (int e = t; e < nblk * OF_NB; e += CHOL_THREADS) {
+    const int b = e >> 4, c = e & 15;
+    const int base = b * OF_NB;
+    double x[OF_NB];
+#pragma unroll
+    for (int r = 0; r < OF_NB; ++r) x[r] = 0.0;
+#pragma unroll
+    for (int r = 0; r < OF_NB; ++r) {
+      if (r == c) {
+        x[r] = dinv[base + c];
+      } else if (r > c) {
+        double s = 0.0;
+#pragma unroll
+        for (int j = 0; j < OF_NB; ++j)
+          if (j >= c && j < r) s += Am[(base + r) * lda + base + j] * x[j];
+        x[r] = -s * dinv[base + r];
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < OF_NB; ++r) Dinv[((int64_t)b * OF_NB + r) * OF_NB + c] = x[r];
+  }
+  OF_STAMP(4);
+  if (LDS_MODE) {
+    // the strict lower triangle is what consumers read; whole rows are copied back
+    const int half = kp >> 1;
+#pragma unroll 8
+    for (int e = t; e < kp * half; e += CHOL_THREADS) {
+      const int i = e / half, j2 = e - i * half;
+      *(double2*)(G + (int64_t)i * kp + 2 * j2) = *(const double2*)(Am + i * lda + 2 * j2);
+    }
+  }
+  OF_STAMP(5);
+  if (t == 0 && deficient && status) atomicOr(status, LORACT_STATUS_RANK_DEFICIENT);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Q = Y R^{-1} with R = L^T, as a blocked triangular solve per 16-row strip (one wave each):
+//   for J = 0 .. NJ-1:   T = Y[:, J] - sum_{I < J} Q[:, I] R[I, J];   Q[:, J] = T R[J, J]^{-1}
+// evaluated transposed (Q_J^T = Linv_JJ (Y_J^T - sum_I L[J, I] Q_I^T)) so that each finished
+// 16 x 16 block of Q^T stays in the accumulator layout and is reused directly as the B operand.
+
+struct TrsmArgs {
+  const float* Y;       // m x kp, ld = ldy
+  int64_t ldy;
+  const double* L;      // kp x kp, strict lower triangle valid
+  const double* Dinv;   // NJ blocks of 16 x 16
+  int64_t m;
+  int kp;
+  int k;
+  void* Q;              // output
+  int64_t ldq;
+  int out_ek;           // EK_F32 (all kp columns written) or EK_BF16 / EK_F32 final (k columns)
+  int out_cols;         // number of columns to write (kp or k)
+  bf16_t* Qb;           // optional second bf16 copy (ld = ldqb, out_cols columns), may be null
+  int64_t ldqb;
+};
+
+template <int NJ>
+__global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
+  const int lane = threadIdx.x;
+  const int lc = lane & 15, lr = lane >> 4;
+  const int64_t row = (int64_t)blockIdx.x * 16 + lc;
+  const bool rok = row < g.m;
+  const float* yrow = g.Y + (rok ? row : 0) * g.ldy;
+  f64x4 qb[NJ];
+#pragma unroll
+  for (int J = 0; J < NJ; ++J) {
+    f64x4 s = (f64x4){0.0, 0.0, 0.0, 0.0};
+    const double* lrow = g.L + (int64_t)(16 * J + lc) * g.kp;
+#pragma unroll
+    for (int I = 0; I < J; ++I) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) s = mfma_f64(lrow[16 * I + 4 * r + lr], qb[I][r], s);
+    }
+    f64x4 tt;
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+      tt[r] = (rok ? (double)yrow[16 * J + 4 * r + lr] : 0.0) - s[r];
+    f64x4 o = (f64x4){0.0, 0.0, 0.0, 0.0};
+    const double* drow = g.Dinv + ((int64_t)J * 16 + lc) * 16;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) o = mfma_f64(drow[4 * r + lr], tt[r], o);
+    qb[J] = o;
+    if (rok) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int col = 16 * J + 4 * r + lr;
+        if (col < g.out_cols) {
+          if (g.out_ek == EK_F32) ((float*)g.Q)[row * g.ldq + col] = (float)o[r];
+          else ((bf16_t*)g.Q)[row * g.ldq + col] = (bf16_t)(float)o[r];
+          if (g.Qb) g.Qb[row * g.ldqb + col] = (bf16_t)(float)o[r];
+        }
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Host-side launchers.
+
+static int gram_rows_per_chunk(int64_t m, int nblocks) {
+  // aim for ~384 workgroups, at least 32 rows per chunk, at most 128 chunks
+  int64_t chunks = std::max<int64_t>(1, 384 / std::max(1, nblocks));
+  chunks = std::min<int64_t>(chunks, 128);
+  int64_t rows = ceil_div64(m, chunks);
+  rows = std::max<int64_t>(32, ceil_div64(rows, 16) * 16);
+  return (int)rows;
+}
+static int gram_nblocks(int kp) {
+  const int nb64 = (kp + 63) / 64;
+  return nb64 * (nb64 + 1) / 2;
+}
+static size_t gram_partial_bytes(int64_t m, int kp) {
+  const int nblocks = gram_nblocks(kp);
+  const int rows = gram_rows_per_chunk(m, nblocks);
+  return (size_t)ceil_div64(m, rows) * nblocks * 4096 * sizeof(double);
+}
+
+static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t m, int kp,
+                            double* part, double* G) {
+  GramArgs g;
+  g.Y = Y; g.ldy = ldy; g.m = m; g.kp = kp;
+  g.nb64 = (kp + 63) / 64;
+  const int nblocks = gram_nblocks(kp);
+  g.rows_per_chunk = gram_rows_per_chunk(m, nblocks);
+  g.part = part;
+  const int chunks = (int)ceil_div64(m, g.rows_per_chunk);
+  LORACT_LAUNCH("gram", s, gram_mfma_kernel, dim3(chunks, nblocks), dim3(256), 0, g);
+  LORACT_LAUNCH("gram_reduce", s, gram_reduce_kernel, dim3(16, nblocks), dim3(256), 0,
+                (const double*)part, chunks, nblocks, kp, G);
+  return LORACT_OK;
+}
+
+static bool g_chol_lds_attr_set = false;
+
+static size_t chol_lds_bytes(int kp, bool lds_mode) {
+  const int ptld = kp > OF_NB ? kp - OF_NB : 2;
+  size_t doubles = (size_t)2 * kp + 8 + (size_t)OF_NB * ptld;
+  if (lds_mode) doubles += (size_t)kp * (kp + 2);
+  return doubles * sizeof(double);
+}
+
+static int launch_chol_blocked(hipStream_t s, double* G, double* Dinv, int k, int kp,
+                               double shift_rel, int32_t* status) {
+  const double tol = ((double)k * 5.9604644775390625e-08) * ((double)k * 5.9604644775390625e-08);
+  if (kp <= 128) {
+    const size_t lds = chol_lds_bytes(kp, true);
+    if (lds > 64 * 1024 && !g_chol_lds_attr_set) {
+      hipError_t e = hipFuncSetAttribute((const void*)chol_blocked_kernel<true>,
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
+      if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(chol LDS)");
+      g_chol_lds_attr_set = true;
+    }
+    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(CHOL_THREADS), lds, G, Dinv, k,
+                  kp, tol, shift_rel, status);
+  } else {
+    const size_t lds = chol_lds_bytes(kp, false);
+    LORACT_LAUNCH("chol", s, chol_blocked_kernel<false>, dim3(1), dim3(CHOL_THREADS), lds, G, Dinv,
+                  k, kp, tol, shift_rel, status);
+  }
+  return LORACT_OK;
+}
+
+template <int NJ>
+static int launch_trsm_nj(hipStream_t s, const TrsmArgs& g) {
+  LORACT_LAUNCH("trsm_apply", s, trsm_apply_kernel<NJ>, dim3((unsigned)ceil_div64(g.m, 16)), dim3(64),
+                0, g);
+  return LORACT_OK;
+}
+
+static int launch_trsm_apply(hipStream_t s, const TrsmArgs& g) {
+  switch (g.kp / 16) {
+#define TRSM_CASE(N) case N: return launch_trsm_nj<N>(s, g);
+    TRSM_CASE(1) TRSM_CASE(2) TRSM_CASE(3) TRSM_CASE(4) TRSM_CASE(5) TRSM_CASE(6) TRSM_CASE(7)
+    TRSM_CASE(8) TRSM_CASE(9) TRSM_CASE(10) TRSM_CASE(11) TRSM_CASE(12) TRSM_CASE(13)
+    TRSM_CASE(14) TRSM_CASE(15) TRSM_CASE(16) TRSM_CASE(17) TRSM_CASE(18) TRSM_CASE(19)
+    TRSM_CASE(20)
+#undef TRSM_CASE
+    default: return LORACT_ERR_UNSUPPORTED;
+  }
+}

@@ -1,0 +1,608 @@
+// Streaming bf16 kernels of the hot path: the passes over the activation X (tokens x hidden)
+// and the write of its reconstruction, on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.
+//
+//   sketch       Y = X Bt^T          Algorithm 1 step 2 (Bt = sampled rows of X) and step 5
+//   project      V = Q^T X           Algorithm 1 step 8 (and step 5)
+//   reconstruct  Xhat = U V          Section 3.1 Eq. (4)
+//
+// All three stage 64-deep K slabs through double-buffered LDS and give each of the 4 waves of
+// a workgroup a 64-row strip of accumulator tiles.  Operands whose contraction index is
+// contiguous in memory (rows of X in the sketch, rows of U in the reconstruction) are stored in
+// LDS as [row][K] and read back as 16-byte MFMA fragments.  Operands whose contraction index is
+// the row index of a row-major matrix (both operands of the projection, V in the
+// reconstruction) are stored "pair interleaved": LDS word [p][c] holds rows 2p and 2p+1 of
+// column c, so that four 4-byte LDS reads give a lane the 8 consecutive-K values of its column
+// with no register shuffling.
+//
+// Fast-path requirements (checked by the host, which otherwise falls back to gemm_bf16.h):
+// 16-byte aligned base pointers and leading dimensions that are multiples of 8 elements.
+#pragma once
+#include "common.h"
+#include <stdlib.h>
+
+#define SB_BM 128
+#define SB_BK 64
+#define SB_LDT 72   // bf16 elements per LDS row of a [row][K] tile (64 + 8 pad)
+
+// Split reductions (over K in the sketch, over the rows in the projection) leave fp32 partial
+// tiles in a scratch buffer; this kernel sums them in ascending split order, so the result does
+// not depend on scheduling, and converts to the output type.  `count` and `ld*` in elements;
+// the row length `cols` is a multiple of 4.
+__global__ __launch_bounds__(256) void sum_partials_kernel(const float* part, int splits,
+                                                           int64_t rows, int64_t cols,
+                                                           int64_t ld_part, void* out,
+                                                           int64_t ld_out, int out_ek) {
+  const int64_t c4 = cols >> 2;
+  const int64_t total = rows * c4;
+  const int64_t split_stride = rows * ld_part;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int64_t r = e / c4, c = (e - r * c4) << 2;
+    const float* src = part + r * ld_part + c;
+    f32x4 s4 = *(const f32x4*)src;
+    for (int z = 1; z < splits; ++z) s4 += *(const f32x4*)(src + (int64_t)z * split_stride);
+    if (out_ek == EK_F32) {
+      *(f32x4*)((float*)out + r * ld_out + c) = s4;
+    } else {
+      bf16x4 o;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) o[u] = (bf16_t)s4[u];
+      *(bf16x4*)((bf16_t*)out + r * ld_out + c) = o;
+    }
+  }
+}
+
+static int launch_sum_partials(hipStream_t s, const float* part, int splits, int64_t rows,
+                               int64_t cols, int64_t ld_part, void* out, int64_t ld_out,
+                               int out_ek) {
+  const int64_t total = rows * (cols >> 2);
+  const int blocks = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(total, 256), 2048));
+  LORACT_LAUNCH("sum_partials", s, sum_partials_kernel, dim3(blocks), dim3(256), 0, part, splits,
+                rows, cols, ld_part, out, ld_out, out_ek);
+  return LORACT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
+// sketch: Y (m x kp, fp32) = X (m x n) * Bt^T, Bt = l rows of length n (optionally gathered).
+
+struct SketchArgs {
+  const bf16_t* X;
+  int64_t ldx;
+  int64_t m, n;
+  const bf16_t* B;
+  int64_t ldb;
+  const int32_t* b_rows;
+  int l;                 // valid rows of Bt
+  int kp;                // columns of Y (l rounded up to 16), columns >= l come out zero
+  float* Y;
+  float* part;           // [splits][m][kp], used when splits > 1
+  int splits;
+  int64_t k_per_split;   // multiple of SB_BK
+};
+
+template <int NT>
+__global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
+  constexpr int BN = 64 * NT;
+  extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
+  bf16_t* As = (bf16_t*)sb_smem;                        // [2][SB_BM][SB_LDT]
+  bf16_t* Bs = As + 2 * SB_BM * SB_LDT;                 // [2][BN][SB_LDT]
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t row0 = (int64_t)blockIdx.x * SB_BM;
+  const int col0 = blockIdx.y * BN;
+  const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+  const int64_t kend = (kbeg + g.k_per_split < g.n) ? kbeg + g.k_per_split : g.n;
+  const int nslab = (int)((kend - kbeg + SB_BK - 1) / SB_BK);
+
+  // per-thread global source rows (fixed over the K loop)
+  const bf16_t* a_src[4];
+  bool a_ok[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int c = t + 256 * i;
+    const int64_t r = row0 + (c >> 3);
+    a_ok[i] = r < g.m;
+    a_src[i] = g.X + (a_ok[i] ? r : 0) * g.ldx + (c & 7) * 8;
+  }
+  // B tile: BN rows x 8 chunks = 512 * NT chunks, 2 * NT per thread
+  const bf16_t* bsrc[2 * NT];
+  bool bok[2 * NT];
+#pragma unroll
+  for (int i = 0; i < 2 * NT; ++i) {
+    const int c = t + 256 * i;
+    const int j = col0 + (c >> 3);
+    bok[i] = j < g.l;
+    int64_t r = 0;
+    if (bok[i]) r = g.b_rows ? (int64_t)g.b_rows[j] : (int64_t)j;
+    bsrc[i] = g.B + r * g.ldb + (c & 7) * 8;
+  }
+
+  f32x16 acc[2][NT];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
+                        (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f};
+  // Two register sets hold the slabs in flight from HBM: while slab s is multiplied out of LDS,
+  // slab s+1 (already requested) is moved to the other LDS buffer and slab s+2 is requested.
+  bf16x8 ra0[4], rb0[2 * NT], ra1[4], rb1[2 * NT];
+  auto gload = [&](bf16x8* ra, bf16x8* rb, int slab) {
+    const int64_t k0 = kbeg + (int64_t)slab * SB_BK;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int64_t kk = k0 + ((t + 256 * i) & 7) * 8;
+      ra[i] = (slab < nslab && a_ok[i] && kk + 8 <= kend) ? *(const bf16x8*)(a_src[i] + k0) : zero8;
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * NT; ++i) {
+      const int64_t kk = k0 + ((t + 256 * i) & 7) * 8;
+      rb[i] = (slab < nslab && bok[i] && kk + 8 <= kend) ? *(const bf16x8*)(bsrc[i] + k0) : zero8;
+    }
+  };
+  auto lstore = [&](const bf16x8* ra, const bf16x8* rb, int buf) {
+    bf16_t* Ab = As + buf * SB_BM * SB_LDT;
+    bf16_t* Bb = Bs + buf * BN * SB_LDT;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int c = t + 256 * i;
+      *(bf16x8*)(Ab + (c >> 3) * SB_LDT + (c & 7) * 8) = ra[i];
+    }
+#pragma unroll
+    for (int i = 0; i < 2 * NT; ++i) {
+      const int c = t + 256 * i;
+      *(bf16x8*)(Bb + (c >> 3) * SB_LDT + (c & 7) * 8) = rb[i];
+    }
+  };
+  auto compute = [&](int buf) {
+    const bf16_t* Ab = As + buf * SB_BM * SB_LDT + (wm * 64 + (lane & 31)) * SB_LDT + 8 * (lane >> 5);
+    const bf16_t* Bb = Bs + buf * BN * SB_LDT + (wn * 32 * NT + (lane & 31)) * SB_LDT + 8 * (lane >> 5);
+#pragma unroll
+    for (int ks = 0; ks < SB_BK; ks += 16) {
+      bf16x8 a[2], b[NT];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) a[i] = *(const bf16x8*)(Ab + i * 32 * SB_LDT + ks);
+#pragma unroll
+      for (int j = 0; j < NT; ++j) b[j] = *(const bf16x8*)(Bb + j * 32 * SB_LDT + ks);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < NT; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+  };
+
+  gload(ra0, rb0, 0);
+  gload(ra1, rb1, 1);
+  lstore(ra0, rb0, 0);
+  __syncthreads();
+  for (int s = 0; s < nslab; s += 2) {
+    gload(ra0, rb0, s + 2);
+    compute(0);
+    if (s + 1 < nslab) lstore(ra1, rb1, 1);
+    __syncthreads();
+    if (s + 1 >= nslab) break;
+    gload(ra1, rb1, s + 3);
+    compute(1);
+    if (s + 2 < nslab) lstore(ra0, rb0, 0);
+    __syncthreads();
+  }
+
+  // epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
+  float* dst = g.splits > 1 ? g.part + (int64_t)blockIdx.z * g.m * g.kp : g.Y;
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < NT; ++j) {
+      const int col = col0 + wn * 32 * NT + 32 * j + (lane & 31);
+      if (col >= g.kp) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int64_t row = row0 + wm * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (row < g.m) dst[row * g.kp + col] = acc[i][j][r];
+      }
+    }
+}
+
+static size_t sketch_lds_bytes(int nt) { return (size_t)2 * (SB_BM + 64 * nt) * SB_LDT * sizeof(bf16_t); }
+
+static inline int sketch_nt_for(int kp) { return kp <= 64 ? 1 : (kp <= 128 ? 2 : 4); }
+
+// Number of K splits: fill ~256-512 workgroups, at least 512 columns per split.
+static inline int sketch_splits_for(int64_t m, int64_t n, int kp) {
+  if (getenv("LORACT_DEBUG_NOSPLIT")) return 1;
+  const int nt = sketch_nt_for(kp);
+  const int64_t tiles = ceil_div64(m, SB_BM) * ceil_div64(kp, 64 * nt);
+  int64_t s = std::max<int64_t>(1, 384 / std::max<int64_t>(1, tiles));
+  s = std::min<int64_t>(s, std::max<int64_t>(1, n / 512));
+  return (int)std::min<int64_t>(s, 16);
+}
+
+static inline bool sb_aligned(const void* p, int64_t ld) {
+  return (((uintptr_t)p) % 16 == 0) && (ld % 8 == 0);
+}
+
+template <int NT>
+static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid) {
+  static bool attr_done = false;
+  const size_t lds = sketch_lds_bytes(NT);
+  if (lds > 64 * 1024 && !attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(sketch LDS)");
+    attr_done = true;
+  }
+  LORACT_LAUNCH("sketch", s, sketch_mfma_kernel<NT>, grid, dim3(256), lds, g);
+  return LORACT_OK;
+}
+
+// part must hold splits * m * kp floats when splits > 1.
+static int launch_sketch_mfma(hipStream_t s, SketchArgs g) {
+  const int nt = sketch_nt_for(g.kp);
+  int64_t kps = ceil_div64(ceil_div64(g.n, g.splits), SB_BK) * SB_BK;
+  g.splits = (int)ceil_div64(g.n, kps);
+  g.k_per_split = kps;
+  dim3 grid((unsigned)ceil_div64(g.m, SB_BM), (unsigned)ceil_div64(g.kp, 64 * nt), (unsigned)g.splits);
+  int rc;
+  switch (nt) {
+    case 1: rc = launch_sketch_nt<1>(s, g, grid); break;
+    case 2: rc = launch_sketch_nt<2>(s, g, grid); break;
+    default: rc = launch_sketch_nt<4>(s, g, grid); break;
+  }
+  if (rc != LORACT_OK || g.splits == 1) return rc;
+  return launch_sum_partials(s, g.part, g.splits, g.m, g.kp, g.kp, g.Y, g.kp, EK_F32);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Pair-interleaved staging of a row-major slab whose rows are the contraction index.
+
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Rows 2p (lo) and 2p+1 (hi), 8 consecutive columns each -> 8 words (col c: lo[c] | hi[c] << 16).
+__device__ inline void sb_interleave(const bf16x8 lo, const bf16x8 hi, u32x4* w0, u32x4* w1) {
+  const u32x4 l = __builtin_bit_cast(u32x4, lo), h = __builtin_bit_cast(u32x4, hi);
+  u32x4 a, b;
+  a[0] = (l[0] & 0xffffu) | (h[0] << 16);  a[1] = (l[0] >> 16) | (h[0] & 0xffff0000u);
+  a[2] = (l[1] & 0xffffu) | (h[1] << 16);  a[3] = (l[1] >> 16) | (h[1] & 0xffff0000u);
+  b[0] = (l[2] & 0xffffu) | (h[2] << 16);  b[1] = (l[2] >> 16) | (h[2] & 0xffff0000u);
+  b[2] = (l[3] & 0xffffu) | (h[3] << 16);  b[3] = (l[3] >> 16) | (h[3] & 0xffff0000u);
+  *w0 = a;
+  *w1 = b;
+}
+
+// MFMA fragment (8 consecutive-K values of one column) from a pair-interleaved tile:
+// words [p0 .. p0+3][col], row stride ldw words.
+__device__ inline bf16x8 sb_pair_frag(const unsigned int* tile, int ldw, int p0, int col) {
+  u32x4 w;
+  w[0] = tile[(p0 + 0) * ldw + col];
+  w[1] = tile[(p0 + 1) * ldw + col];
+  w[2] = tile[(p0 + 2) * ldw + col];
+  w[3] = tile[(p0 + 3) * ldw + col];
+  return __builtin_bit_cast(bf16x8, w);
+}
+
+// ---------------------------------------------------------------------------------------------
+// project: V (l x n) = Q^T X with Q (m x l, bf16, ld = ldq) and X (m x n): long reduction over
+// the rows, split across workgroups; each workgroup owns a (BMQ x 128) tile of V for its rows.
+
+#define PJ_BN 128
+#define PJ_LDX (PJ_BN + 4)     // words per pair-row of the X slab
+
+struct ProjectArgs {
+  const bf16_t* Q;
+  int64_t ldq;
+  const bf16_t* X;
+  int64_t ldx;
+  int64_t m, n;
+  int l;                   // columns of Q = rows of V
+  void* V;                 // l x n, ld = n
+  int out_ek;              // EK_BF16 or EK_F32
+  float* part;             // [splits][l][n]
+  int splits;
+  int64_t rows_per_split;  // multiple of SB_BK
+};
+
+template <int NTQ>
+__global__ __launch_bounds__(256) void project_mfma_kernel(ProjectArgs g) {
+  constexpr int BMQ = 64 * NTQ;
+  constexpr int LDQW = BMQ + 4;
+  extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
+  unsigned int* Qs = (unsigned int*)sb_smem;            // [2][32][LDQW]
+  unsigned int* Xs = Qs + 2 * 32 * LDQW;                // [2][32][PJ_LDX]
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t col0 = (int64_t)blockIdx.x * PJ_BN;
+  const int q0 = blockIdx.y * BMQ;
+  const int64_t rbeg = (int64_t)blockIdx.z * g.rows_per_split;
+  const int64_t rend = (rbeg + g.rows_per_split < g.m) ? rbeg + g.rows_per_split : g.m;
+  const int nslab = (int)((rend - rbeg + SB_BK - 1) / SB_BK);
+
+  // X slab: 32 pair-rows x 16 chunks = 512 pair-chunks, 2 per thread.
+  // Q slab: 32 pair-rows x BMQ/8 chunks = 256 NTQ pair-chunks, NTQ per thread.
+  bf16x8 xlo[2], xhi[2], qlo[NTQ], qhi[NTQ];
+  const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
+                        (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f};
+  auto gload = [&](int64_t r0) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = t + 256 * i;
+      const int p = c >> 4, ch = c & 15;
+      const int64_t r = r0 + 2 * p, col = col0 + ch * 8;
+      const bool cok = col + 8 <= g.n;
+      const bf16_t* src = g.X + r * g.ldx + col;
+      xlo[i] = (cok && r < rend) ? *(const bf16x8*)src : zero8;
+      xhi[i] = (cok && r + 1 < rend) ? *(const bf16x8*)(src + g.ldx) : zero8;
+    }
+#pragma unroll
+    for (int i = 0; i < NTQ; ++i) {
+      const int c = t + 256 * i;
+      const int p = c / (BMQ / 8), ch = c % (BMQ / 8);
+      const int64_t r = r0 + 2 * p;
+      const int qc = q0 + ch * 8;
+      const bool cok = qc + 8 <= g.l;
+      const bf16_t* src = g.Q + r * g.ldq + qc;
+      qlo[i] = (cok && r < rend) ? *(const bf16x8*)src : zero8;
+      qhi[i] = (cok && r + 1 < rend) ? *(const bf16x8*)(src + g.ldq) : zero8;
+    }
+  };
+  auto lstore = [&](int buf) {
+    unsigned int* Xb = Xs + buf * 32 * PJ_LDX;
+    unsigned int* Qb = Qs + buf * 32 * LDQW;
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+      const int c = t + 256 * i;
+      u32x4 w0, w1;
+      sb_interleave(xlo[i], xhi[i], &w0, &w1);
+      unsigned int* d = Xb + (c >> 4) * PJ_LDX + (c & 15) * 8;
+      *(u32x4*)d = w0;
+      *(u32x4*)(d + 4) = w1;
+    }
+#pragma unroll
+    for (int i = 0; i < NTQ; ++i) {
+      const int c = t + 256 * i;
+      u32x4 w0, w1;
+      sb_interleave(qlo[i], qhi[i], &w0, &w1);
+      unsigned int* d = Qb + (c / (BMQ / 8)) * LDQW + (c % (BMQ / 8)) * 8;
+      *(u32x4*)d = w0;
+      *(u32x4*)(d + 4) = w1;
+    }
+  };
+
+  f32x16 acc[NTQ][2];
+#pragma unroll
+  for (int i = 0; i < NTQ; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+  gload(rbeg);
+  lstore(0);
+  __syncthreads();
+  for (int s = 0; s < nslab; ++s) {
+    const int cur = s & 1;
+    if (s + 1 < nslab) gload(rbeg + (int64_t)(s + 1) * SB_BK);
+    const unsigned int* Xb = Xs + cur * 32 * PJ_LDX;
+    const unsigned int* Qb = Qs + cur * 32 * LDQW;
+#pragma unroll
+    for (int ks = 0; ks < SB_BK; ks += 16) {
+      const int p0 = (ks >> 1) + 4 * (lane >> 5);
+      bf16x8 a[NTQ], b[2];
+#pragma unroll
+      for (int i = 0; i < NTQ; ++i) a[i] = sb_pair_frag(Qb, LDQW, p0, wm * 32 * NTQ + 32 * i + (lane & 31));
+#pragma unroll
+      for (int j = 0; j < 2; ++j) b[j] = sb_pair_frag(Xb, PJ_LDX, p0, wn * 64 + 32 * j + (lane & 31));
+#pragma unroll
+      for (int i = 0; i < NTQ; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
+    }
+    if (s + 1 < nslab) lstore(cur ^ 1);
+    __syncthreads();
+  }
+
+  // partial tile: rows = columns of Q, columns = columns of X
+  float* dst = g.part + (int64_t)blockIdx.z * g.l * g.n;
+#pragma unroll
+  for (int i = 0; i < NTQ; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      const int64_t col = col0 + wn * 64 + 32 * j + (lane & 31);
+      if (col >= g.n) continue;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) {
+        const int q = q0 + wm * 32 * NTQ + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        if (q < g.l) dst[(int64_t)q * g.n + col] = acc[i][j][r];
+      }
+    }
+}
+
+static inline int project_ntq_for(int l) { return l <= 64 ? 1 : (l <= 128 ? 2 : 4); }
+static size_t project_lds_bytes(int ntq) {
+  return (size_t)2 * 32 * ((64 * ntq + 4) + PJ_LDX) * sizeof(unsigned int);
+}
+static inline int project_splits_for(int64_t m, int64_t n, int l) {
+  if (getenv("LORACT_DEBUG_NOSPLIT")) return 1;
+  const int ntq = project_ntq_for(l);
+  const int64_t tiles = ceil_div64(n, PJ_BN) * ceil_div64(l, 64 * ntq);
+  int64_t s = std::max<int64_t>(1, 512 / std::max<int64_t>(1, tiles));
+  s = std::min<int64_t>(s, std::max<int64_t>(1, m / 256));
+  return (int)std::min<int64_t>(s, 64);
+}
+
+template <int NTQ>
+static int launch_project_ntq(hipStream_t s, const ProjectArgs& g, dim3 grid) {
+  static bool attr_done = false;
+  const size_t lds = project_lds_bytes(NTQ);
+  if (lds > 64 * 1024 && !attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(project LDS)");
+    attr_done = true;
+  }
+  LORACT_LAUNCH("project", s, project_mfma_kernel<NTQ>, grid, dim3(256), lds, g);
+  return LORACT_OK;
+}
+
+// part: splits * l * n floats.
+static int launch_project_mfma(hipStream_t s, ProjectArgs g) {
+  const int ntq = project_ntq_for(g.l);
+  int64_t rps = ceil_div64(ceil_div64(g.m, g.splits), SB_BK) * SB_BK;
+  g.splits = (int)ceil_div64(g.m, rps);
+  g.rows_per_split = rps;
+  dim3 grid((unsigned)ceil_div64(g.n, PJ_BN), (unsigned)ceil_div64(g.l, 64 * ntq), (unsigned)g.splits);
+  int rc;
+  switch (ntq) {
+    case 1: rc = launch_project_ntq<1>(s, g, grid); break;
+    case 2: rc = launch_project_ntq<2>(s, g, grid); break;
+    default: rc = launch_project_ntq<4>(s, g, grid); break;
+  }
+  if (rc != LORACT_OK) return rc;
+  return launch_sum_partials(s, g.part, g.splits, g.l, g.n, g.n, g.V, g.n, g.out_ek);
+}
+
+// ---------------------------------------------------------------------------------------------
+// reconstruct: Xhat (m x n, bf16) = U (m x k) V (k x n).  A workgroup owns 128 columns: it stages
+// its V tile once (pair interleaved), then walks over row tiles of 128 rows.  The product is
+// formed transposed (rows of the MFMA tile = columns of Xhat) so that the U fragments come
+// straight from global memory as 16-byte loads; the finished tile is turned back through LDS and
+// written as full 256-byte row segments.
+
+#define RC_BN 128
+#define RC_LDV (RC_BN + 4)   // words per pair-row of the V tile
+#define RC_LDC (RC_BN + 8)   // bf16 elements per row of the output staging tile
+
+struct ReconArgs {
+  const bf16_t* U;       // m x k, ld = k
+  const bf16_t* V;       // k x n, ld = n
+  int64_t m, n;
+  int k;
+  bf16_t* Xhat;
+  int64_t ldxh;
+  int row_tiles;         // ceil(m / 128)
+};
+
+template <int NKS>   // number of 16-deep K steps = ceil(k / 16)
+__global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
+  unsigned int* Vs = (unsigned int*)sb_smem;                       // [NKS * 8][RC_LDV]
+  bf16_t* Cs = (bf16_t*)(Vs + NKS * 8 * RC_LDV);                   // [128][RC_LDC]
+
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t col0 = (int64_t)blockIdx.x * RC_BN;
+  const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
+                        (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f};
+
+  // stage V[:, col0 .. col0+128) pair interleaved
+  for (int c = t; c < NKS * 8 * 16; c += 256) {
+    const int p = c >> 4, ch = c & 15;
+    const int64_t col = col0 + ch * 8;
+    const bool cok = col + 8 <= g.n;
+    const bf16_t* src = g.V + (int64_t)(2 * p) * g.n + col;
+    const bf16x8 lo = (cok && 2 * p < g.k) ? *(const bf16x8*)src : zero8;
+    const bf16x8 hi = (cok && 2 * p + 1 < g.k) ? *(const bf16x8*)(src + g.n) : zero8;
+    u32x4 w0, w1;
+    sb_interleave(lo, hi, &w0, &w1);
+    unsigned int* d = Vs + p * RC_LDV + ch * 8;
+    *(u32x4*)d = w0;
+    *(u32x4*)(d + 4) = w1;
+  }
+  __syncthreads();
+
+  for (int rt = blockIdx.y; rt < g.row_tiles; rt += gridDim.y) {
+    const int64_t r0 = (int64_t)rt * 128;
+    // U fragments of this wave's 64 rows, all K steps
+    bf16x8 b[NKS][2];
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int64_t row = r0 + wn * 64 + 32 * j + (lane & 31);
+        const int kk = ks * 16 + 8 * (lane >> 5);
+        b[ks][j] = (row < g.m && kk + 8 <= g.k) ? *(const bf16x8*)(g.U + row * g.k + kk) : zero8;
+      }
+    f32x16 acc[2][2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+#pragma unroll
+    for (int ks = 0; ks < NKS; ++ks) {
+      bf16x8 a[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+        a[i] = sb_pair_frag(Vs, RC_LDV, ks * 8 + 4 * (lane >> 5), wm * 64 + 32 * i + (lane & 31));
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[ks][j], acc[i][j], 0, 0, 0);
+    }
+    // accumulator register r of lane l: column 8*(r/4) + 4*(l/32) + r%4 of Xhat, row l%32
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < 2; ++j)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          bf16x4 o;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) o[u] = (bf16_t)acc[i][j][4 * q + u];
+          const int row = wn * 64 + 32 * j + (lane & 31);
+          const int col = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
+          *(bf16x4*)(Cs + row * RC_LDC + col) = o;
+        }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      const int e = t + 256 * q;
+      const int row = e >> 4, ch = e & 15;
+      const int64_t grow = r0 + row, col = col0 + ch * 8;
+      if (grow < g.m && col + 8 <= g.n)
+        *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = *(const bf16x8*)(Cs + row * RC_LDC + ch * 8);
+    }
+    __syncthreads();
+  }
+}
+
+static size_t reconstruct_lds_bytes(int nks) {
+  return (size_t)nks * 8 * RC_LDV * sizeof(unsigned int) + (size_t)128 * RC_LDC * sizeof(bf16_t);
+}
+
+template <int NKS>
+static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) {
+  static bool attr_done = false;
+  const size_t lds = reconstruct_lds_bytes(NKS);
+  if (lds > 64 * 1024 && !attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)reconstruct_mfma_kernel<NKS>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(reconstruct LDS)");
+    attr_done = true;
+  }
+  LORACT_LAUNCH("reconstruct", s, reconstruct_mfma_kernel<NKS>, grid, dim3(256), lds, g);
+  return LORACT_OK;
+}
+
+static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
+  g.row_tiles = (int)ceil_div64(g.m, 128);
+  const int64_t colb = ceil_div64(g.n, RC_BN);
+  int64_t groups = std::max<int64_t>(1, 768 / colb);
+  groups = std::min<int64_t>(groups, g.row_tiles);
+  dim3 grid((unsigned)colb, (unsigned)groups);
+  switch ((g.k + 15) / 16) {
+#define RC_CASE(N) case N: return launch_reconstruct_nks<N>(s, g, grid);
+    RC_CASE(1) RC_CASE(2) RC_CASE(3) RC_CASE(4) RC_CASE(5) RC_CASE(6) RC_CASE(7) RC_CASE(8)
+    RC_CASE(9) RC_CASE(10) RC_CASE(11) RC_CASE(12) RC_CASE(13) RC_CASE(14) RC_CASE(15)
+    RC_CASE(16) RC_CASE(17) RC_CASE(18) RC_CASE(19) RC_CASE(20)
+#undef RC_CASE
+    default: return LORACT_ERR_UNSUPPORTED;
+  }
+}
