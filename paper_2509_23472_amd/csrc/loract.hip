@@ -182,7 +182,7 @@ static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows
   const int64_t m = c.p->m, n = c.p->n;
   const int l = c.pl.l;
   if (c.pl.bf16_path) {
-    if (sb_aligned(c.X, c.p->ldx) && sb_aligned(Bt, ldb) && n % 8 == 0) {
+    if (sb_aligned(c.X, c.p->ldx) && sb_aligned(Bt, ldb) && n % 64 == 0) {
       SketchArgs a;
       a.X = (const bf16_t*)c.X; a.ldx = c.p->ldx; a.m = m; a.n = n;
       a.B = (const bf16_t*)Bt; a.ldb = ldb; a.b_rows = rows; a.l = l; a.kp = c.pl.kp;

@@ -167,13 +167,13 @@ __device__ inline double rsqrt_f64(double x) {
   return y;
 }
 
-#define CHOL_THREADS 512
 
+// LDS mode runs 4 waves (the pivot chains are latency bound, more waves only add contention);
+// global mode runs 8 waves to overlap the memory latency of the trailing-block updates.
 template <bool LDS_MODE>
-__global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, double* Dinv, int k,
-                                                                    int kp, double tol,
-                                                                    double shift_rel,
-                                                                    int32_t* status) {
+__global__ __launch_bounds__(LDS_MODE ? 256 : 512) void chol_blocked_kernel(
+    double* G, double* Dinv, int k, int kp, double tol, double shift_rel, int32_t* status) {
+  constexpr int CHOL_THREADS = LDS_MODE ? 256 : 512;
   extern __shared__ double smem[];
   // layout: gdiag[kp] | dinv[kp] | misc[8] | Pt[16][kp - 16] | (LDS mode) A[kp][kp + 2]
   double* gdiag = smem;            // original diagonal
@@ -182,13 +182,13 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
   const int ptld = kp > OF_NB ? kp - OF_NB : 2;
   double* Pt = smem + 2 * kp + 8;  // panel below the diagonal block, transposed: Pt[p][row - below]
   double* Am = LDS_MODE ? (Pt + OF_NB * ptld) : G;
-  const int lda = LDS_MODE ? kp + 2 : kp;
+  const int lda = LDS_MODE ? kp + 1 : kp;   // odd pitch: column walks hit distinct banks
   __shared__ int deficient;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   OF_STAMP(0);
 #ifdef OF_TIMING
-  long long t_panel = 0, t_trail = 0, t_mark = 0;
+  long long t_panel = 0, t_trail = 0, t_mark = 0, t_pl = 0, t_pc = 0, t_ps = 0, t_m2 = 0;
 #endif
   if (LDS_MODE) {
     // kp is a multiple of 16: copy whole rows two doubles at a time
@@ -197,7 +197,8 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
     for (int e = t; e < kp * half; e += CHOL_THREADS) {
       const int i = e / half, j2 = e - i * half;
       const double2 v = *(const double2*)(G + (int64_t)i * kp + 2 * j2);
-      *(double2*)(Am + i * lda + 2 * j2) = v;
+      Am[i * lda + 2 * j2] = v.x;
+      Am[i * lda + 2 * j2 + 1] = v.y;
     }
   }
   for (int i = t; i < kp; i += CHOL_THREADS) gdiag[i] = G[(int64_t)i * kp + i];
@@ -224,19 +225,30 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
 
     // ---- panel: one row per lane, its 16 panel entries in registers.  Lanes 0..15 of every
     // wave hold the diagonal block (redundantly), lanes 16..63 hold 48 of the rows below.
-    const int row = (lane < 16) ? (jb + lane) : (below + wave * 48 + lane - 16);
-    const bool row_ok = row < kp;
-    double a[OF_NB];
+    // 4 waves x 48 rows per pass; a second pass (kp > 208) reuses the saved diagonal block
+    constexpr int NWAVES = CHOL_THREADS / 64;
+    const int npass = nrows_below > 0 ? (nrows_below + 48 * NWAVES - 1) / (48 * NWAVES) : 1;
+    double dsave[OF_NB];
     double thr[OF_NB];
 #pragma unroll
     for (int c = 0; c < OF_NB; ++c) {
       double v = 0.0;
-      if (row_ok && (lane >= 16 || c <= lane)) v = Am[row * lda + jb + c];
+      if (lane < 16 && c <= lane) v = Am[(jb + lane) * lda + jb + c];
       if (lane < 16 && c == lane) v += shift;
-      a[c] = v;
+      dsave[c] = v;
       thr[c] = tol * gdiag[jb + c];
     }
     __syncthreads();   // every wave has read the unfactored diagonal block
+    for (int pass = 0; pass < npass; ++pass) {
+    const int row = (lane < 16) ? (jb + lane) : (below + (pass * NWAVES + wave) * 48 + lane - 16);
+    const bool row_ok = row < kp;
+    double a[OF_NB];
+#pragma unroll
+    for (int c = 0; c < OF_NB; ++c)
+      a[c] = (lane < 16) ? dsave[c] : (row_ok ? Am[row * lda + jb + c] : 0.0);
+#ifdef OF_TIMING
+    { long long now = wall_clock64(); t_pl += now - t_mark; t_m2 = now; }
+#endif
     double dval[OF_NB];
     bool any_bad = false;
     if (!OF_SKIPPED(1))
@@ -254,6 +266,9 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
         a[c] = fma(-a[j], lcj, a[c]);
       }
     }
+#ifdef OF_TIMING
+    { long long now = wall_clock64(); t_pc += now - t_m2; t_m2 = now; }
+#endif
     if (lane >= 16) {
       if (row_ok) {
 #pragma unroll
@@ -262,7 +277,7 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
           Pt[c * ptld + row - below] = a[c];
         }
       }
-    } else if (wave == 0) {   // wave 0 owns the diagonal block
+    } else if (wave == 0 && pass == 0) {   // wave 0 owns the diagonal block
 #pragma unroll
       for (int c = 0; c < OF_NB; ++c)
         if (c < lane) Am[row * lda + jb + c] = a[c];
@@ -272,45 +287,36 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
         if (any_bad) deficient = 1;
       }
     }
+    }
     __syncthreads();
 #ifdef OF_TIMING
-    { long long now = wall_clock64(); t_panel += now - t_mark; t_mark = now; }
+    { long long now = wall_clock64(); t_ps += now - t_m2; t_panel += now - t_mark; t_mark = now; }
 #endif
 
-    // ---- trailing update of the lower triangle, 4 x 4 tiles
-    const int nt = nrows_below / 4;
-    const int ntiles = nt * (nt + 1) / 2;
-    for (int e = t; e < ntiles && !OF_SKIPPED(2); e += CHOL_THREADS) {
-      int ti = (int)((sqrtf(8.0f * (float)e + 1.0f) - 1.0f) * 0.5f);
-      while (ti * (ti + 1) / 2 > e) --ti;
-      while ((ti + 1) * (ti + 2) / 2 <= e) ++ti;
-      const int tc = e - ti * (ti + 1) / 2;
-      double acc[4][4];
+    // ---- trailing update of the lower triangle: A[I][C] -= P_I P_C^T per 16 x 16 block (C <= I),
+    // one block per wave at a time on the float64 matrix cores, the panel read from Pt.
+    {
+      const int nb16 = nrows_below / OF_NB;
+      const int nblocks = nb16 * (nb16 + 1) / 2;
+      const int lc = lane & 15, lr = lane >> 4;
+      for (int e = wave; e < nblocks && !OF_SKIPPED(2); e += CHOL_THREADS / 64) {
+        int ti = (int)((sqrtf(8.0f * (float)e + 1.0f) - 1.0f) * 0.5f);
+        while (ti * (ti + 1) / 2 > e) --ti;
+        while ((ti + 1) * (ti + 2) / 2 <= e) ++ti;
+        const int tc = e - ti * (ti + 1) / 2;
+        double* ablk = Am + (below + OF_NB * ti + lr) * lda + below + OF_NB * tc + lc;
+        f64x4 acc;
+        double pa[4], pb[4];
 #pragma unroll
-      for (int x = 0; x < 4; ++x)
+        for (int r = 0; r < 4; ++r) {
+          acc[r] = ablk[4 * r * lda];
+          pa[r] = -Pt[(4 * r + lr) * ptld + OF_NB * ti + lc];
+          pb[r] = Pt[(4 * r + lr) * ptld + OF_NB * tc + lc];
+        }
 #pragma unroll
-        for (int y = 0; y < 4; ++y) acc[x][y] = 0.0;
-#pragma unroll 4
-      for (int p = 0; p < OF_NB; ++p) {
-        const double2 pi01 = *(const double2*)(Pt + p * ptld + 4 * ti);
-        const double2 pi23 = *(const double2*)(Pt + p * ptld + 4 * ti + 2);
-        const double2 pc01 = *(const double2*)(Pt + p * ptld + 4 * tc);
-        const double2 pc23 = *(const double2*)(Pt + p * ptld + 4 * tc + 2);
-        const double pi[4] = {pi01.x, pi01.y, pi23.x, pi23.y};
-        const double pc[4] = {pc01.x, pc01.y, pc23.x, pc23.y};
+        for (int r = 0; r < 4; ++r) acc = mfma_f64(pa[r], pb[r], acc);
 #pragma unroll
-        for (int x = 0; x < 4; ++x)
-#pragma unroll
-          for (int y = 0; y < 4; ++y) acc[x][y] = fma(pi[x], pc[y], acc[x][y]);
-      }
-      const int i0 = below + 4 * ti, c0 = below + 4 * tc;
-#pragma unroll
-      for (int x = 0; x < 4; ++x) {
-        double* dst = Am + (i0 + x) * lda + c0;
-        double2 v01 = *(double2*)dst, v23 = *(double2*)(dst + 2);
-        v01.x -= acc[x][0]; v01.y -= acc[x][1]; v23.x -= acc[x][2]; v23.y -= acc[x][3];
-        *(double2*)dst = v01;
-        *(double2*)(dst + 2) = v23;
+        for (int r = 0; r < 4; ++r) ablk[4 * r * lda] = acc[r];
       }
     }
     __syncthreads();
@@ -320,28 +326,25 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
   }
   OF_STAMP(3);
 #ifdef OF_TIMING
-  if (t == 0) { of_stamps[10] = t_panel; of_stamps[11] = t_trail; }
+  if (t == 0) { of_stamps[10] = t_panel; of_stamps[11] = t_trail; of_stamps[12] = t_pl; of_stamps[13] = t_pc; of_stamps[14] = t_ps; }
 #endif
 
-  // ---- inverses of the 16 x 16 diagonal blocks, one thread per (block, column)
+  // ---- inverses of the 16 x 16 diagonal blocks, one thread per (block, column c):
+  // column c of L_bb^{-1} by forward substitution in update form (x_j is final after step j and
+  // is then subtracted from all later rows at once, so the 15 steps carry a two-operation chain).
   const int nblk = kp / OF_NB;
   for (int e = t; e < nblk * OF_NB; e += CHOL_THREADS) {
     const int b = e >> 4, c = e & 15;
     const int base = b * OF_NB;
-    double x[OF_NB];
+    double acc[OF_NB], x[OF_NB];
 #pragma unroll
-    for (int r = 0; r < OF_NB; ++r) x[r] = 0.0;
+    for (int r = 0; r < OF_NB; ++r) acc[r] = (r == c) ? 1.0 : 0.0;
 #pragma unroll
-    for (int r = 0; r < OF_NB; ++r) {
-      if (r == c) {
-        x[r] = dinv[base + c];
-      } else if (r > c) {
-        double s = 0.0;
+    for (int j = 0; j < OF_NB; ++j) {
+      const double xj = (j >= c) ? acc[j] * dinv[base + j] : 0.0;
+      x[j] = xj;
 #pragma unroll
-        for (int j = 0; j < OF_NB; ++j)
-          if (j >= c && j < r) s += Am[(base + r) * lda + base + j] * x[j];
-        x[r] = -s * dinv[base + r];
-      }
+      for (int r = j + 1; r < OF_NB; ++r) acc[r] = fma(-Am[(base + r) * lda + base + j], xj, acc[r]);
     }
 #pragma unroll
     for (int r = 0; r < OF_NB; ++r) Dinv[((int64_t)b * OF_NB + r) * OF_NB + c] = x[r];
@@ -353,7 +356,10 @@ __global__ __launch_bounds__(CHOL_THREADS) void chol_blocked_kernel(double* G, d
 #pragma unroll 8
     for (int e = t; e < kp * half; e += CHOL_THREADS) {
       const int i = e / half, j2 = e - i * half;
-      *(double2*)(G + (int64_t)i * kp + 2 * j2) = *(const double2*)(Am + i * lda + 2 * j2);
+      double2 v;
+      v.x = Am[i * lda + 2 * j2];
+      v.y = Am[i * lda + 2 * j2 + 1];
+      *(double2*)(G + (int64_t)i * kp + 2 * j2) = v;
     }
   }
   OF_STAMP(5);
@@ -463,7 +469,7 @@ static bool g_chol_lds_attr_set = false;
 static size_t chol_lds_bytes(int kp, bool lds_mode) {
   const int ptld = kp > OF_NB ? kp - OF_NB : 2;
   size_t doubles = (size_t)2 * kp + 8 + (size_t)OF_NB * ptld;
-  if (lds_mode) doubles += (size_t)kp * (kp + 2);
+  if (lds_mode) doubles += (size_t)kp * (kp + 1);
   return doubles * sizeof(double);
 }
 
@@ -478,12 +484,12 @@ static int launch_chol_blocked(hipStream_t s, double* G, double* Dinv, int k, in
       if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(chol LDS)");
       g_chol_lds_attr_set = true;
     }
-    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(CHOL_THREADS), lds, G, Dinv, k,
-                  kp, tol, shift_rel, status);
+    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(256), lds, G, Dinv, k, kp, tol,
+                  shift_rel, status);
   } else {
     const size_t lds = chol_lds_bytes(kp, false);
-    LORACT_LAUNCH("chol", s, chol_blocked_kernel<false>, dim3(1), dim3(CHOL_THREADS), lds, G, Dinv,
-                  k, kp, tol, shift_rel, status);
+    LORACT_LAUNCH("chol", s, chol_blocked_kernel<false>, dim3(1), dim3(512), lds, G, Dinv, k, kp,
+                  tol, shift_rel, status);
   }
   return LORACT_OK;
 }

@@ -62,7 +62,34 @@ static int launch_sum_partials(hipStream_t s, const float* part, int splits, int
 }
 
 // ---------------------------------------------------------------------------------------------
+// Asynchronous global -> LDS copies (global_load_lds_dwordx4): every lane of a wave fetches 16
+// bytes from its own global address and the wave's 64 pieces land contiguously (lane i at
+// base + 16 i) in LDS, without passing through registers.  Several slabs can therefore be in
+// flight from HBM per workgroup at no register cost; s_waitcnt vmcnt tracks their arrival.
+// Because the LDS placement is fixed by the lane number, bank conflicts are avoided by choosing
+// WHICH global chunk each lane fetches (an XOR swizzle on the chunk index), not by padding.
+
+__device__ inline void sb_async16(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding).
+#define SB_WAIT_VMCNT(n) \
+  __builtin_amdgcn_s_waitcnt(((n) & 15) | ((((n) >> 4) & 3) << 14) | (7 << 4) | (15 << 8))
+
+// Workgroup barrier that orders LDS traffic for the compiler but does not drain the vector-memory
+// queue: __syncthreads() would wait for every outstanding asynchronous copy and with it for the
+// slabs that are meant to stay in flight.  Callers first wait (SB_WAIT_VMCNT) for the copies they
+// are about to read; LDS reads of the slab being recycled have completed by then because their
+// results were consumed by matrix instructions earlier in program order.
+__device__ inline void sb_barrier_keep_copies() { asm volatile("s_barrier" ::: "memory"); }
+
+// ---------------------------------------------------------------------------------------------
 // sketch: Y (m x kp, fp32) = X (m x n) * Bt^T, Bt = l rows of length n (optionally gathered).
+//
+// LDS slab layout, both operands: [row][64 K] as 8 chunks of 16 bytes per 128-byte row, chunk c of
+// row r stored at position c ^ (r & 7), so that the 16-byte fragment reads of 8 consecutive rows
+// hit 8 different bank groups.  Requires n % 64 == 0 (no partial slab) on this path.
 
 struct SketchArgs {
   const bf16_t* X;
@@ -77,45 +104,63 @@ struct SketchArgs {
   float* part;           // [splits][m][kp], used when splits > 1
   int splits;
   int64_t k_per_split;   // multiple of SB_BK
+  int dbg;               // development switches (0 in production)
 };
 
-template <int NT>
+template <int NT, int STAGES>
 __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
   constexpr int BN = 64 * NT;
+  constexpr int A_BYTES = SB_BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int LOADS = 4 + 2 * NT;     // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
-  bf16_t* As = (bf16_t*)sb_smem;                        // [2][SB_BM][SB_LDT]
-  bf16_t* Bs = As + 2 * SB_BM * SB_LDT;                 // [2][BN][SB_LDT]
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t row0 = (int64_t)blockIdx.x * SB_BM;
-  const int col0 = blockIdx.y * BN;
-  const int64_t kbeg = (int64_t)blockIdx.z * g.k_per_split;
+  const int64_t row0 = (int64_t)blockIdx.y * SB_BM;
+  const int col0 = blockIdx.z * BN;
+  // Split z owns a contiguous K range.  Each workgroup walks its slabs starting from a different
+  // offset (rotated by its row-tile index): with a power-of-two row pitch, workgroups that all read
+  // the same K offset at the same time would crowd a few memory channels.
+  const int zsplit = blockIdx.x;
+  const int64_t kbeg = (int64_t)zsplit * g.k_per_split;
   const int64_t kend = (kbeg + g.k_per_split < g.n) ? kbeg + g.k_per_split : g.n;
-  const int nslab = (int)((kend - kbeg + SB_BK - 1) / SB_BK);
+  const int nslab = (int)((kend - kbeg) / SB_BK);
+  const int rot = nslab > 0 ? (int)(blockIdx.y % nslab) : 0;
 
-  // per-thread global source rows (fixed over the K loop)
+  // global sources of this lane's chunks (rows past the end are clamped: they only feed
+  // accumulator rows / columns that are never stored)
+  const int sub = lane >> 3;                       // row within the 8-row group = row & 7
+  const int kc = (lane & 7) ^ sub;                 // swizzled K chunk fetched by this lane
   const bf16_t* a_src[4];
-  bool a_ok[4];
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int c = t + 256 * i;
-    const int64_t r = row0 + (c >> 3);
-    a_ok[i] = r < g.m;
-    a_src[i] = g.X + (a_ok[i] ? r : 0) * g.ldx + (c & 7) * 8;
+    int64_t r = row0 + (wave * 4 + i) * 8 + sub;
+    if (r >= g.m) r = g.m - 1;
+    a_src[i] = g.X + r * g.ldx + kbeg + kc * 8;
   }
-  // B tile: BN rows x 8 chunks = 512 * NT chunks, 2 * NT per thread
-  const bf16_t* bsrc[2 * NT];
-  bool bok[2 * NT];
+  const bf16_t* b_src[2 * NT];
 #pragma unroll
   for (int i = 0; i < 2 * NT; ++i) {
-    const int c = t + 256 * i;
-    const int j = col0 + (c >> 3);
-    bok[i] = j < g.l;
+    const int j = col0 + (wave * 2 * NT + i) * 8 + sub;
     int64_t r = 0;
-    if (bok[i]) r = g.b_rows ? (int64_t)g.b_rows[j] : (int64_t)j;
-    bsrc[i] = g.B + r * g.ldb + (c & 7) * 8;
+    if (j < g.l) r = g.b_rows ? (int64_t)g.b_rows[j] : (int64_t)j;
+    else r = g.b_rows ? (int64_t)g.b_rows[0] : 0;
+    b_src[i] = g.B + r * g.ldb + kbeg + kc * 8;
   }
+  auto issue = [&](int slab) {
+    unsigned char* st = sb_smem + (slab % STAGES) * STAGE_BYTES;
+    if (g.dbg & 8) return;
+    int pos = slab + rot;
+    if (pos >= nslab) pos -= nslab;
+    const int64_t koff = (int64_t)pos * SB_BK;
+    const int64_t koff_a = (g.dbg & 1) ? 0 : koff;
+    const int64_t koff_b = (g.dbg & 2) ? 0 : koff;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) sb_async16(a_src[i] + koff_a, st + (wave * 4 + i) * 1024);
+#pragma unroll
+    for (int i = 0; i < 2 * NT; ++i)
+      sb_async16(b_src[i] + koff_b, st + A_BYTES + (wave * 2 * NT + i) * 1024);
+  };
 
   f32x16 acc[2][NT];
 #pragma unroll
@@ -125,98 +170,74 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
-  const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
-                        (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f};
-  // Two register sets hold the slabs in flight from HBM: while slab s is multiplied out of LDS,
-  // slab s+1 (already requested) is moved to the other LDS buffer and slab s+2 is requested.
-  bf16x8 ra0[4], rb0[2 * NT], ra1[4], rb1[2 * NT];
-  auto gload = [&](bf16x8* ra, bf16x8* rb, int slab) {
-    const int64_t k0 = kbeg + (int64_t)slab * SB_BK;
+  // fragment addresses inside a stage
+  int a_off[2], b_off[NT];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int64_t kk = k0 + ((t + 256 * i) & 7) * 8;
-      ra[i] = (slab < nslab && a_ok[i] && kk + 8 <= kend) ? *(const bf16x8*)(a_src[i] + k0) : zero8;
-    }
+  for (int i = 0; i < 2; ++i) a_off[i] = (wm * 64 + 32 * i + (lane & 31)) * 128;
 #pragma unroll
-    for (int i = 0; i < 2 * NT; ++i) {
-      const int64_t kk = k0 + ((t + 256 * i) & 7) * 8;
-      rb[i] = (slab < nslab && bok[i] && kk + 8 <= kend) ? *(const bf16x8*)(bsrc[i] + k0) : zero8;
-    }
-  };
-  auto lstore = [&](const bf16x8* ra, const bf16x8* rb, int buf) {
-    bf16_t* Ab = As + buf * SB_BM * SB_LDT;
-    bf16_t* Bb = Bs + buf * BN * SB_LDT;
+  for (int j = 0; j < NT; ++j) b_off[j] = A_BYTES + (wn * 32 * NT + 32 * j + (lane & 31)) * 128;
+  const int rsw = lane & 7;                        // (row & 7) of every fragment row of this lane
+  const int khalf = lane >> 5;
+
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int c = t + 256 * i;
-      *(bf16x8*)(Ab + (c >> 3) * SB_LDT + (c & 7) * 8) = ra[i];
-    }
+  for (int p = 0; p < STAGES - 1; ++p)
+    if (p < nslab) issue(p);
+  for (int s = 0; s < nslab; ++s) {
+    // slab s has landed once at most the copies of the (STAGES - 2) younger slabs are pending
+    if (s + STAGES - 1 <= nslab) SB_WAIT_VMCNT((STAGES - 2) * LOADS);
+    else SB_WAIT_VMCNT(0);
+    sb_barrier_keep_copies();                      // everyone's copies landed; slab s-1 is consumed
+    if (s + STAGES - 1 < nslab) issue(s + STAGES - 1);
+    const unsigned char* st = sb_smem + (s % STAGES) * STAGE_BYTES;
+    if (g.dbg & 4) continue;
 #pragma unroll
-    for (int i = 0; i < 2 * NT; ++i) {
-      const int c = t + 256 * i;
-      *(bf16x8*)(Bb + (c >> 3) * SB_LDT + (c & 7) * 8) = rb[i];
-    }
-  };
-  auto compute = [&](int buf) {
-    const bf16_t* Ab = As + buf * SB_BM * SB_LDT + (wm * 64 + (lane & 31)) * SB_LDT + 8 * (lane >> 5);
-    const bf16_t* Bb = Bs + buf * BN * SB_LDT + (wn * 32 * NT + (lane & 31)) * SB_LDT + 8 * (lane >> 5);
-#pragma unroll
-    for (int ks = 0; ks < SB_BK; ks += 16) {
+    for (int ks = 0; ks < 4; ++ks) {
+      const int pos = ((2 * ks + khalf) ^ rsw) << 4;
       bf16x8 a[2], b[NT];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *(const bf16x8*)(Ab + i * 32 * SB_LDT + ks);
+      for (int i = 0; i < 2; ++i) a[i] = *(const bf16x8*)(st + a_off[i] + pos);
 #pragma unroll
-      for (int j = 0; j < NT; ++j) b[j] = *(const bf16x8*)(Bb + j * 32 * SB_LDT + ks);
+      for (int j = 0; j < NT; ++j) b[j] = *(const bf16x8*)(st + b_off[j] + pos);
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
     }
-  };
-
-  gload(ra0, rb0, 0);
-  gload(ra1, rb1, 1);
-  lstore(ra0, rb0, 0);
-  __syncthreads();
-  for (int s = 0; s < nslab; s += 2) {
-    gload(ra0, rb0, s + 2);
-    compute(0);
-    if (s + 1 < nslab) lstore(ra1, rb1, 1);
-    __syncthreads();
-    if (s + 1 >= nslab) break;
-    gload(ra1, rb1, s + 3);
-    compute(1);
-    if (s + 2 < nslab) lstore(ra0, rb0, 0);
-    __syncthreads();
   }
 
   // epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
-  float* dst = g.splits > 1 ? g.part + (int64_t)blockIdx.z * g.m * g.kp : g.Y;
+  float* dst = g.splits > 1 ? g.part + (int64_t)zsplit * g.m * g.kp : g.Y;
+  if (g.dbg & 16) return;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const int col = col0 + wn * 32 * NT + 32 * j + (lane & 31);
       if (col >= g.kp) continue;
+      const bool live = col < g.l;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int64_t row = row0 + wm * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < g.m) dst[row * g.kp + col] = acc[i][j][r];
+        if (row < g.m) dst[row * g.kp + col] = live ? acc[i][j][r] : 0.0f;
       }
     }
 }
 
-static size_t sketch_lds_bytes(int nt) { return (size_t)2 * (SB_BM + 64 * nt) * SB_LDT * sizeof(bf16_t); }
+static inline int sketch_stages_for(int nt) { return nt == 4 ? 3 : 4; }
+static size_t sketch_lds_bytes(int nt) {
+  return (size_t)sketch_stages_for(nt) * (SB_BM + 64 * nt) * 128;
+}
 
 static inline int sketch_nt_for(int kp) { return kp <= 64 ? 1 : (kp <= 128 ? 2 : 4); }
 
 // Number of K splits: fill ~256-512 workgroups, at least 512 columns per split.
 static inline int sketch_splits_for(int64_t m, int64_t n, int kp) {
-  if (getenv("LORACT_DEBUG_NOSPLIT")) return 1;
+  if (getenv("LORACT_DEBUG_SKETCH_SPLITS")) return atoi(getenv("LORACT_DEBUG_SKETCH_SPLITS"));
   const int nt = sketch_nt_for(kp);
   const int64_t tiles = ceil_div64(m, SB_BM) * ceil_div64(kp, 64 * nt);
-  int64_t s = std::max<int64_t>(1, 384 / std::max<int64_t>(1, tiles));
+  // one workgroup per CU (the multi-stage LDS pipeline fills a CU's LDS), at least 512 columns each
+  int64_t s = std::max<int64_t>(1, 256 / std::max<int64_t>(1, tiles));
   s = std::min<int64_t>(s, std::max<int64_t>(1, n / 512));
   return (int)std::min<int64_t>(s, 16);
 }
@@ -230,12 +251,12 @@ static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid) {
   static bool attr_done = false;
   const size_t lds = sketch_lds_bytes(NT);
   if (lds > 64 * 1024 && !attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT>,
+    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, (NT == 4 ? 3 : 4)>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(sketch LDS)");
     attr_done = true;
   }
-  LORACT_LAUNCH("sketch", s, sketch_mfma_kernel<NT>, grid, dim3(256), lds, g);
+  LORACT_LAUNCH("sketch", s, (sketch_mfma_kernel<NT, (NT == 4 ? 3 : 4)>), grid, dim3(256), lds, g);
   return LORACT_OK;
 }
 
@@ -245,7 +266,9 @@ static int launch_sketch_mfma(hipStream_t s, SketchArgs g) {
   int64_t kps = ceil_div64(ceil_div64(g.n, g.splits), SB_BK) * SB_BK;
   g.splits = (int)ceil_div64(g.n, kps);
   g.k_per_split = kps;
-  dim3 grid((unsigned)ceil_div64(g.m, SB_BM), (unsigned)ceil_div64(g.kp, 64 * nt), (unsigned)g.splits);
+  g.dbg = getenv("LORACT_DEBUG_SKETCH") ? atoi(getenv("LORACT_DEBUG_SKETCH")) : 0;
+  dim3 grid((unsigned)g.splits, (unsigned)ceil_div64(g.m, SB_BM), (unsigned)ceil_div64(g.kp, 64 * nt));
+  if (grid.y > 65535) return LORACT_ERR_UNSUPPORTED;
   int rc;
   switch (nt) {
     case 1: rc = launch_sketch_nt<1>(s, g, grid); break;
@@ -427,7 +450,7 @@ static size_t project_lds_bytes(int ntq) {
   return (size_t)2 * 32 * ((64 * ntq + 4) + PJ_LDX) * sizeof(unsigned int);
 }
 static inline int project_splits_for(int64_t m, int64_t n, int l) {
-  if (getenv("LORACT_DEBUG_NOSPLIT")) return 1;
+  if (getenv("LORACT_DEBUG_PROJECT_SPLITS")) return atoi(getenv("LORACT_DEBUG_PROJECT_SPLITS"));
   const int ntq = project_ntq_for(l);
   const int64_t tiles = ceil_div64(n, PJ_BN) * ceil_div64(l, 64 * ntq);
   int64_t s = std::max<int64_t>(1, 512 / std::max<int64_t>(1, tiles));
