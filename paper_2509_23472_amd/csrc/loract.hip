@@ -419,16 +419,25 @@ int loract_reconstruct(const void* U_dev, const void* V_dev, int64_t m, int64_t 
 // Workspace of loract_lora_grad: G (m x r, fp32 or bf16), T (k x r, fp32), split partials.
 struct LoraPlan {
   int t_splits;
-  size_t off_g, off_t, off_dpart, total;
+  int rp;                 // r rounded up to 16
+  int g_splits, p_splits; // K splits of dY B^T, row splits of U^T G
+  size_t off_g, off_t, off_dpart, off_gpart, off_gsplit, off_ppart, off_tsplit, total;
 };
 static int make_lora_plan(int64_t m, int64_t n, int32_t k, int64_t n_out, int32_t r, LoraPlan* lp) {
   if (m < 1 || n < 1 || k < 1 || n_out < 1 || r < 1 || r > 64) return LORACT_ERR_INVALID_ARG;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   lp->t_splits = pick_splits(ceil_div64(k, 64), m, 128);
-  lp->off_g = take((size_t)m * r * 4);
+  lp->rp = (r + 15) / 16 * 16;
+  lp->g_splits = sketch_splits_for(m, n_out, lp->rp);
+  lp->p_splits = project_splits_for(m, 2 * lp->rp, k);
+  lp->off_g = take((size_t)m * lp->rp * 4);
   lp->off_t = take((size_t)k * r * 4);
   lp->off_dpart = take((size_t)lp->t_splits * k * r * 8);
+  lp->off_gpart = take((size_t)lp->g_splits * m * lp->rp * 4);
+  lp->off_gsplit = take((size_t)m * 2 * lp->rp * 2);
+  lp->off_ppart = take((size_t)lp->p_splits * k * 2 * lp->rp * 4);
+  lp->off_tsplit = take((size_t)k * 2 * lp->rp * 4);
   lp->total = off;
   return LORACT_OK;
 }
@@ -457,19 +466,44 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
   float* T = (float*)(ws + lp.off_t);
   double* dpart = (double*)(ws + lp.off_dpart);
   const int f_ek = factor_dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
+  if (factor_dtype == LORACT_BF16 && grad_dtype == LORACT_BF16 && k <= LORACT_MAX_RANK &&
+      n_out % 64 == 0 && sb_aligned(dY_dev, n_out) && sb_aligned(Blora_dev, n_out) &&
+      sb_aligned(U_dev, k) && sb_aligned(V_dev, n)) {
+    const int rp = lp.rp;
+    // G = dY B_lora^T (m x rp), the one pass over dY, left as the bf16 pair [G_hi | G_lo]
+    SketchArgs a;
+    a.X = (const bf16_t*)dY_dev; a.ldx = n_out; a.m = m; a.n = n_out;
+    a.B = (const bf16_t*)Blora_dev; a.ldb = n_out; a.b_rows = nullptr; a.l = r_lora; a.kp = rp;
+    a.Y = (float*)(ws + lp.off_g); a.part = (float*)(ws + lp.off_gpart); a.splits = lp.g_splits;
+    a.k_per_split = 0;
+    bf16_t* Gsplit = (bf16_t*)(ws + lp.off_gsplit);
+    LORACT_TRY(launch_sketch_mfma(s, a, "lora_dyb", Gsplit));
+    // [T_hi | T_lo] = U^T [G_hi | G_lo]  (k x 2rp)
+    ProjectArgs pa;
+    pa.Q = (const bf16_t*)U_dev; pa.ldq = k; pa.X = Gsplit; pa.ldx = 2 * rp; pa.m = m; pa.n = 2 * rp;
+    pa.l = k; pa.V = ws + lp.off_tsplit; pa.out_ek = EK_F32; pa.part = (float*)(ws + lp.off_ppart);
+    pa.splits = lp.p_splits; pa.rows_per_split = 0;
+    LORACT_TRY(launch_project_mfma(s, pa, "lora_utg"));
+    // dA = scale * V^T (T_hi + T_lo)
+    const int64_t items = n * (rp / 4);
+    LORACT_LAUNCH("lora_vtt", s, lora_vtt_kernel, dim3((unsigned)ceil_div64(items, 256)), dim3(256),
+                  (size_t)k * rp * sizeof(float), (const bf16_t*)V_dev,
+                  (const float*)(ws + lp.off_tsplit), (int)k, n, (int)r_lora, rp, scale, dA_dev);
+    return LORACT_OK;
+  }
   // G = dY B_lora^T  (m x r): the only pass over the large operand
   if (grad_dtype == LORACT_BF16)
-    LORACT_TRY(launch_gemm_bf16("lora_dyb", s, (const bf16_t*)dY_dev, n_out, 1,
+    LORACT_TRY(launch_gemm_bf16("lora_dyb_generic", s, (const bf16_t*)dY_dev, n_out, 1,
                                 (const bf16_t*)Blora_dev, n_out, 1, nullptr, m, r_lora, n_out, G,
                                 r_lora, EK_F32, 1, nullptr));
   else
     LORACT_TRY(launch_gemm_f64("lora_dyb_f64", s, dY_dev, n_out, 1, EK_F32, Blora_dev, n_out, 1,
                                EK_F32, nullptr, m, r_lora, n_out, 1.0, G, r_lora, EK_F32, 1, nullptr));
   // T = U^T G  (k x r)
-  LORACT_TRY(launch_gemm_f64("lora_utg", s, U_dev, k, 0, f_ek, G, r_lora, 0, EK_F32, nullptr, k,
+  LORACT_TRY(launch_gemm_f64("lora_utg_generic", s, U_dev, k, 0, f_ek, G, r_lora, 0, EK_F32, nullptr, k,
                              r_lora, m, 1.0, T, r_lora, EK_F32, lp.t_splits, dpart));
   // dA = V^T T * scale  (n x r)
-  return launch_gemm_f64("lora_vtt", s, V_dev, n, 0, f_ek, T, r_lora, 0, EK_F32, nullptr, n, r_lora,
+  return launch_gemm_f64("lora_vtt_generic", s, V_dev, n, 0, f_ek, T, r_lora, 0, EK_F32, nullptr, n, r_lora,
                          k, (double)scale, dA_dev, r_lora, EK_F32, 1, nullptr);
 }
 

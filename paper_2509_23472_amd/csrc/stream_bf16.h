@@ -18,7 +18,6 @@
 // 16-byte aligned base pointers and leading dimensions that are multiples of 8 elements.
 #pragma once
 #include "common.h"
-#include <stdlib.h>
 
 #define SB_BM 128
 #define SB_BK 64
@@ -26,8 +25,11 @@
 
 // Split reductions (over K in the sketch, over the rows in the projection) leave fp32 partial
 // tiles in a scratch buffer; this kernel sums them in ascending split order, so the result does
-// not depend on scheduling, and converts to the output type.  `count` and `ld*` in elements;
-// the row length `cols` is a multiple of 4.
+// not depend on scheduling, and converts to the output type.  `ld*` in elements; the row length
+// `cols` is a multiple of 4.  Output kinds: fp32, bf16, or EK_BF16_SPLIT: every value v is written
+// as the bf16 pair hi = bf16(v), lo = bf16(v - hi) at columns c and cols + c of a row of 2 * cols
+// bf16 values, so that a bf16 matrix product with the pair recovers ~16 mantissa bits of v.
+#define EK_BF16_SPLIT 3
 __global__ __launch_bounds__(256) void sum_partials_kernel(const float* part, int splits,
                                                            int64_t rows, int64_t cols,
                                                            int64_t ld_part, void* out,
@@ -42,11 +44,20 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* part, in
     for (int z = 1; z < splits; ++z) s4 += *(const f32x4*)(src + (int64_t)z * split_stride);
     if (out_ek == EK_F32) {
       *(f32x4*)((float*)out + r * ld_out + c) = s4;
-    } else {
+    } else if (out_ek == EK_BF16) {
       bf16x4 o;
 #pragma unroll
       for (int u = 0; u < 4; ++u) o[u] = (bf16_t)s4[u];
       *(bf16x4*)((bf16_t*)out + r * ld_out + c) = o;
+    } else {
+      bf16x4 hi, lo;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        hi[u] = (bf16_t)s4[u];
+        lo[u] = (bf16_t)(s4[u] - (float)hi[u]);
+      }
+      *(bf16x4*)((bf16_t*)out + r * ld_out + c) = hi;
+      *(bf16x4*)((bf16_t*)out + r * ld_out + cols + c) = lo;
     }
   }
 }
@@ -104,7 +115,6 @@ struct SketchArgs {
   float* part;           // [splits][m][kp], used when splits > 1
   int splits;
   int64_t k_per_split;   // multiple of SB_BK
-  int dbg;               // development switches (0 in production)
 };
 
 template <int NT, int STAGES>
@@ -149,17 +159,14 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
   }
   auto issue = [&](int slab) {
     unsigned char* st = sb_smem + (slab % STAGES) * STAGE_BYTES;
-    if (g.dbg & 8) return;
     int pos = slab + rot;
     if (pos >= nslab) pos -= nslab;
     const int64_t koff = (int64_t)pos * SB_BK;
-    const int64_t koff_a = (g.dbg & 1) ? 0 : koff;
-    const int64_t koff_b = (g.dbg & 2) ? 0 : koff;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sb_async16(a_src[i] + koff_a, st + (wave * 4 + i) * 1024);
+    for (int i = 0; i < 4; ++i) sb_async16(a_src[i] + koff, st + (wave * 4 + i) * 1024);
 #pragma unroll
     for (int i = 0; i < 2 * NT; ++i)
-      sb_async16(b_src[i] + koff_b, st + A_BYTES + (wave * 2 * NT + i) * 1024);
+      sb_async16(b_src[i] + koff, st + A_BYTES + (wave * 2 * NT + i) * 1024);
   };
 
   f32x16 acc[2][NT];
@@ -189,7 +196,6 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
     sb_barrier_keep_copies();                      // everyone's copies landed; slab s-1 is consumed
     if (s + STAGES - 1 < nslab) issue(s + STAGES - 1);
     const unsigned char* st = sb_smem + (s % STAGES) * STAGE_BYTES;
-    if (g.dbg & 4) continue;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int pos = ((2 * ks + khalf) ^ rsw) << 4;
@@ -208,7 +214,6 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
 
   // epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
   float* dst = g.splits > 1 ? g.part + (int64_t)zsplit * g.m * g.kp : g.Y;
-  if (g.dbg & 16) return;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -233,7 +238,6 @@ static inline int sketch_nt_for(int kp) { return kp <= 64 ? 1 : (kp <= 128 ? 2 :
 
 // Number of K splits: fill ~256-512 workgroups, at least 512 columns per split.
 static inline int sketch_splits_for(int64_t m, int64_t n, int kp) {
-  if (getenv("LORACT_DEBUG_SKETCH_SPLITS")) return atoi(getenv("LORACT_DEBUG_SKETCH_SPLITS"));
   const int nt = sketch_nt_for(kp);
   const int64_t tiles = ceil_div64(m, SB_BM) * ceil_div64(kp, 64 * nt);
   // one workgroup per CU (the multi-stage LDS pipeline fills a CU's LDS), at least 512 columns each
@@ -247,7 +251,7 @@ static inline bool sb_aligned(const void* p, int64_t ld) {
 }
 
 template <int NT>
-static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid) {
+static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const char* name) {
   static bool attr_done = false;
   const size_t lds = sketch_lds_bytes(NT);
   if (lds > 64 * 1024 && !attr_done) {
@@ -256,26 +260,32 @@ static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid) {
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(sketch LDS)");
     attr_done = true;
   }
-  LORACT_LAUNCH("sketch", s, (sketch_mfma_kernel<NT, (NT == 4 ? 3 : 4)>), grid, dim3(256), lds, g);
+  LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, (NT == 4 ? 3 : 4)>), grid, dim3(256), lds, g);
   return LORACT_OK;
 }
 
-// part must hold splits * m * kp floats when splits > 1.
-static int launch_sketch_mfma(hipStream_t s, SketchArgs g) {
+// part must hold splits * m * kp floats when splits > 1.  If `split_out` is given the result is
+// (also for a single split) passed through the partial buffer and written there as the bf16 pair
+// [hi | lo] (m x 2 kp) instead of fp32 Y.
+static int launch_sketch_mfma(hipStream_t s, SketchArgs g, const char* name = "sketch",
+                              bf16_t* split_out = nullptr) {
   const int nt = sketch_nt_for(g.kp);
   int64_t kps = ceil_div64(ceil_div64(g.n, g.splits), SB_BK) * SB_BK;
   g.splits = (int)ceil_div64(g.n, kps);
   g.k_per_split = kps;
-  g.dbg = getenv("LORACT_DEBUG_SKETCH") ? atoi(getenv("LORACT_DEBUG_SKETCH")) : 0;
   dim3 grid((unsigned)g.splits, (unsigned)ceil_div64(g.m, SB_BM), (unsigned)ceil_div64(g.kp, 64 * nt));
   if (grid.y > 65535) return LORACT_ERR_UNSUPPORTED;
+  if (split_out && g.splits == 1) g.Y = g.part;     // single split: Y itself is the "partial"
   int rc;
   switch (nt) {
-    case 1: rc = launch_sketch_nt<1>(s, g, grid); break;
-    case 2: rc = launch_sketch_nt<2>(s, g, grid); break;
-    default: rc = launch_sketch_nt<4>(s, g, grid); break;
+    case 1: rc = launch_sketch_nt<1>(s, g, grid, name); break;
+    case 2: rc = launch_sketch_nt<2>(s, g, grid, name); break;
+    default: rc = launch_sketch_nt<4>(s, g, grid, name); break;
   }
-  if (rc != LORACT_OK || g.splits == 1) return rc;
+  if (rc != LORACT_OK) return rc;
+  if (split_out)
+    return launch_sum_partials(s, g.part, g.splits, g.m, g.kp, g.kp, split_out, 2 * g.kp, EK_BF16_SPLIT);
+  if (g.splits == 1) return rc;
   return launch_sum_partials(s, g.part, g.splits, g.m, g.kp, g.kp, g.Y, g.kp, EK_F32);
 }
 
@@ -450,7 +460,6 @@ static size_t project_lds_bytes(int ntq) {
   return (size_t)2 * 32 * ((64 * ntq + 4) + PJ_LDX) * sizeof(unsigned int);
 }
 static inline int project_splits_for(int64_t m, int64_t n, int l) {
-  if (getenv("LORACT_DEBUG_PROJECT_SPLITS")) return atoi(getenv("LORACT_DEBUG_PROJECT_SPLITS"));
   const int ntq = project_ntq_for(l);
   const int64_t tiles = ceil_div64(n, PJ_BN) * ceil_div64(l, 64 * ntq);
   int64_t s = std::max<int64_t>(1, 512 / std::max<int64_t>(1, tiles));
@@ -459,7 +468,7 @@ static inline int project_splits_for(int64_t m, int64_t n, int l) {
 }
 
 template <int NTQ>
-static int launch_project_ntq(hipStream_t s, const ProjectArgs& g, dim3 grid) {
+static int launch_project_ntq(hipStream_t s, const ProjectArgs& g, dim3 grid, const char* name) {
   static bool attr_done = false;
   const size_t lds = project_lds_bytes(NTQ);
   if (lds > 64 * 1024 && !attr_done) {
@@ -468,12 +477,12 @@ static int launch_project_ntq(hipStream_t s, const ProjectArgs& g, dim3 grid) {
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(project LDS)");
     attr_done = true;
   }
-  LORACT_LAUNCH("project", s, project_mfma_kernel<NTQ>, grid, dim3(256), lds, g);
+  LORACT_LAUNCH(name, s, project_mfma_kernel<NTQ>, grid, dim3(256), lds, g);
   return LORACT_OK;
 }
 
 // part: splits * l * n floats.
-static int launch_project_mfma(hipStream_t s, ProjectArgs g) {
+static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = "project") {
   const int ntq = project_ntq_for(g.l);
   int64_t rps = ceil_div64(ceil_div64(g.m, g.splits), SB_BK) * SB_BK;
   g.splits = (int)ceil_div64(g.m, rps);
@@ -481,9 +490,9 @@ static int launch_project_mfma(hipStream_t s, ProjectArgs g) {
   dim3 grid((unsigned)ceil_div64(g.n, PJ_BN), (unsigned)ceil_div64(g.l, 64 * ntq), (unsigned)g.splits);
   int rc;
   switch (ntq) {
-    case 1: rc = launch_project_ntq<1>(s, g, grid); break;
-    case 2: rc = launch_project_ntq<2>(s, g, grid); break;
-    default: rc = launch_project_ntq<4>(s, g, grid); break;
+    case 1: rc = launch_project_ntq<1>(s, g, grid, name); break;
+    case 2: rc = launch_project_ntq<2>(s, g, grid, name); break;
+    default: rc = launch_project_ntq<4>(s, g, grid, name); break;
   }
   if (rc != LORACT_OK) return rc;
   return launch_sum_partials(s, g.part, g.splits, g.l, g.n, g.n, g.V, g.n, g.out_ek);
@@ -628,4 +637,34 @@ static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
 #undef RC_CASE
     default: return LORACT_ERR_UNSUPPORTED;
   }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Last contraction of the LoRA gradient: dA (n x r) = scale * V^T (T_hi + T_lo), with V (k x n,
+// bf16) and the k x 2rp fp32 matrix [T_hi | T_lo] produced by the split-bf16 projection.
+// One thread per (column of V, group of 4 output columns); T is staged in LDS.
+
+__global__ __launch_bounds__(256) void lora_vtt_kernel(const bf16_t* V, const float* Tsplit,
+                                                       int k, int64_t n, int r, int rp,
+                                                       float scale, float* dA) {
+  extern __shared__ float lv_T[];   // [k][rp]
+  for (int e = threadIdx.x; e < k * rp; e += 256) {
+    const int q = e / rp, c = e - q * rp;
+    lv_T[e] = Tsplit[(int64_t)q * 2 * rp + c] + Tsplit[(int64_t)q * 2 * rp + rp + c];
+  }
+  __syncthreads();
+  const int groups = rp >> 2;
+  const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  const int64_t j = item % n;                 // consecutive threads -> consecutive columns of V
+  const int cg = (int)(item / n);
+  if (cg >= groups) return;
+  f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
+  for (int q = 0; q < k; ++q) {
+    const float v = (float)V[(int64_t)q * n + j];
+    const f32x4 tq = *(const f32x4*)(lv_T + q * rp + 4 * cg);
+    acc += v * tq;
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (4 * cg + u < r) dA[j * r + 4 * cg + u] = scale * acc[u];
 }
