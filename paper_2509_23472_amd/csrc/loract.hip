@@ -5,6 +5,7 @@
 #include "chol.h"
 #include "ortho_f64.h"
 #include "stream_bf16.h"
+#include "eig_jacobi.h"
 
 #include <algorithm>
 #include <cmath>
@@ -89,7 +90,7 @@ struct Plan {
   int gram_splits, proj_splits;
   size_t off_idx, off_a, off_b, off_ub, off_g, off_rinv, off_dpart, off_fpart, off_zt;
   size_t off_bmat, off_eig, off_omega, off_dinv;
-  int sketch_splits;
+  int sketch_splits, bgram_splits;
   size_t total;
 };
 
@@ -140,6 +141,11 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
+  pl->bgram_splits = 1;
+  if (rsvd && l > p->k) {
+    pl->bgram_splits = pick_splits(lt * lt, n, 256);
+    dpart = std::max(dpart, (size_t)pl->bgram_splits * l * l * 8);
+  }
   pl->off_dpart = take(dpart);
   size_t fpart = 0;
   pl->sketch_splits = 1;
@@ -520,9 +526,63 @@ int loract_gaussian_omega_t(void* omegaT_dev, int32_t l, int64_t n, int32_t dtyp
 
 int loract_rsvd(const void* X_dev, const loract_params* p, const void* omegaT_dev, void* U_dev,
                 void* V_dev, void* ws_dev, size_t ws_bytes, void* stream, int32_t* status_dev) {
-  (void)X_dev; (void)p; (void)omegaT_dev; (void)U_dev; (void)V_dev; (void)ws_dev; (void)ws_bytes;
-  (void)stream; (void)status_dev;
-  return LORACT_ERR_NOT_IMPLEMENTED;
+  Ctx c;
+  hipStream_t s = (hipStream_t)stream;
+  LORACT_TRY(check_common(X_dev, p, U_dev, V_dev, ws_dev, ws_bytes, true, &c, s, status_dev));
+  const int64_t m = p->m, n = p->n;
+  const int k = p->k, l = c.pl.l;
+  // clear the status word (no sampled rows on this path)
+  IdxPack pack;
+  memset(&pack, 0, sizeof(pack));
+  LORACT_LAUNCH("store_indices", s, store_indices_kernel, dim3(1), dim3(256), 0, pack, 0,
+                ws_ptr<int32_t>(c, c.pl.off_idx), status_dev);
+  // Gaussian test matrix, stored transposed (l x n) in X's element type
+  const void* omega = omegaT_dev;
+  if (!omega) {
+    void* om = c.ws + c.pl.off_omega;
+    LORACT_TRY(loract_gaussian_omega_t(om, l, n, p->x_dtype, p->seed, stream));
+    omega = om;
+  }
+  void* Y = c.ws + c.pl.off_a;
+  void* tmp = c.ws + c.pl.off_b;
+  if (c.pl.bf16_path) {
+    LORACT_TRY(sketch(c, omega, n, nullptr, Y));                       // Y = X Omega
+  } else {
+    // fp32 input: the generic product reads Omega in its own element type
+    LORACT_TRY(launch_gemm_f64("sketch_f64", s, X_dev, p->ldx, 1, EK_F32, omega, n, 1, EK_F32, nullptr,
+                               m, l, n, 1.0, Y, l, EK_F64, 1, nullptr));
+  }
+  LORACT_TRY(power_iterations(c, Y, tmp));                             // t x [QR; Y = X (X^T Q)]
+  if (l == k) return finish_factors(c, Y, tmp, U_dev, V_dev);          // no oversampling: U = Q, V = Q^T X
+
+  // oversampled: B = Q^T X (l x n), then truncate to the k leading singular triplets of B
+  const int f_ek = p->factor_dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
+  void* Bmat = c.ws + c.pl.off_bmat;
+  const void* Q;
+  int q_ek, b_ek;
+  if (c.pl.bf16_path) {
+    // Q in fp32 (into the sketch buffer, free by the second round) for U = Q W_k, and its bf16
+    // copy for the projection on the matrix cores
+    bf16_t* Qb = ws_ptr<bf16_t>(c, c.pl.off_ub);
+    LORACT_TRY(orthonormalise_mfma(c, (const float*)Y, (float*)tmp, Y, EK_F32, Qb));
+    LORACT_TRY(project(c, Qb, EK_BF16, Bmat, EK_F32));
+    Q = Y; q_ek = EK_F32; b_ek = EK_F32;
+  } else {
+    LORACT_TRY(orthonormalise(c, Y, tmp, Y, EK_F64));
+    LORACT_TRY(project(c, Y, EK_F64, Bmat, EK_F64));
+    Q = Y; q_ek = EK_F64; b_ek = EK_F64;
+  }
+  double* eigA = ws_ptr<double>(c, c.pl.off_eig);
+  double* eigW = eigA + (size_t)l * l;
+  double* Wk = eigW + (size_t)l * l;
+  LORACT_TRY(launch_gemm_f64("rsvd_bbt", s, Bmat, n, 1, b_ek, Bmat, n, 1, b_ek, nullptr, l, l, n, 1.0,
+                             eigA, l, EK_F64, c.pl.bgram_splits, ws_ptr<double>(c, c.pl.off_dpart)));
+  LORACT_TRY(launch_jacobi_eig(s, eigA, eigW, Wk, l, k));
+  // U = Q W_k (m x k),  V = W_k^T B (k x n)
+  LORACT_TRY(launch_gemm_f64("rsvd_qw", s, Q, l, 1, q_ek, Wk, k, 0, EK_F64, nullptr, m, k, l, 1.0,
+                             U_dev, k, f_ek, 1, nullptr));
+  return launch_gemm_f64("rsvd_wtb", s, Wk, k, 0, EK_F64, Bmat, n, 0, b_ek, nullptr, k, n, l, 1.0,
+                         V_dev, n, f_ek, 1, nullptr);
 }
 
 int loract_profile_begin(void) {

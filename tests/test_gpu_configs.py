@@ -73,3 +73,26 @@ def test_c5_long_context_site():
     print("oracle decompose %.1fs" % (time.time() - t0), flush=True)
     res = check_compress_parity(w, u, v, xhat, oracle_factors=(uo, vo), strict_ortho=True)
     print("c5", res, "status", status)
+
+
+def test_c4_rsvd_comparator():
+    # config 4: same rank, oversampling 8, one power iteration, Gaussian test matrix from the seed
+    import paper_2509_23472_amd as L
+    w = synth.c4_mlp()
+    p, q = w.extras["oversample"], w.extras["power_iters"]
+    x = to_device(w.x, w.dtype)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    u, v = L.loract_rsvd(x, w.k, oversample=p, power_iters=q, seed=w.seed, status=status)
+    torch.cuda.synchronize()
+    t0 = time.time()
+    omega_t = synth.round_to_bf16(orc.gaussian_omega_t(w.k + p, w.n, w.seed).astype(np.float32))
+    uo, vo = orc.rsvd(w.x.astype(np.float64), w.k, oversample=p, power_iters=q,
+                      omega_t=omega_t.astype(np.float64))
+    print("oracle rsvd %.1fs" % (time.time() - t0), flush=True)
+    res = check_compress_parity(w, u, v, oracle_factors=(uo, vo), strict_ortho=True)
+    print("c4 rsvd", res, "status", int(status.item()))
+    # both methods at equal rank on the same input: comparable approximation quality (Section 3.2)
+    ul, vl = L.loract_compress(x, w.k, seed=w.seed)
+    torch.cuda.synchronize()
+    e_loract = orc.rel_fro(to_host(ul) @ to_host(vl), w.x.astype(np.float64))
+    print("quality: loract %.4e  rsvd %.4e" % (e_loract, res["quality_gpu"]))

@@ -247,3 +247,43 @@ def test_gaussian_generator_matches_oracle_definition():
     torch.cuda.synchronize()
     assert np.max(np.abs(to_host(g32) - ref)) <= 1e-6
     assert np.max(np.abs(to_host(g16) - ref) / (np.abs(ref) + 1e-3)) <= 2.0 ** -8
+
+
+# ----------------------------------------------------------------------------- RSVD comparator
+
+
+@pytest.mark.parametrize("dtype,m,n,k,oversample,iters", [
+    ("f32", 300, 128, 12, 0, 0), ("f32", 300, 128, 12, 5, 1),
+    ("bf16", 640, 256, 24, 0, 0), ("bf16", 640, 256, 24, 8, 0), ("bf16", 700, 320, 40, 8, 1),
+])
+def test_rsvd_comparator_matches_oracle(dtype, m, n, k, oversample, iters):
+    # Section 3.2's comparator, with the Gaussian test matrix handed to both sides as data.
+    L = _lib()
+    w = _spectrum_workload(m, n, k, seed=5 * m + k + oversample, dtype=dtype, decay=0.85)
+    l = k + oversample
+    omega_t = synth.gaussian_test_matrix(l, n, seed=77 + oversample).astype(np.float32)
+    if dtype == "bf16":
+        omega_t = synth.round_to_bf16(omega_t)
+    x = to_device(w.x, dtype)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    u, v = L.loract_rsvd(x, k, oversample=oversample, power_iters=iters,
+                         omega_t=to_device(omega_t, dtype), status=status)
+    torch.cuda.synchronize()
+    uo, vo = orc.rsvd(w.x.astype(np.float64), k, oversample=oversample, power_iters=iters,
+                      omega_t=omega_t.astype(np.float64))
+    res = check_compress_parity(w, u, v, oracle_factors=(uo, vo),
+                                tol=1e-4 if dtype == "f32" else None)
+    print(res, "status", int(status.item()))
+    assert int(status.item()) == 0
+
+
+def test_rsvd_with_device_generated_test_matrix():
+    # seed-derived Gaussian test matrix: both sides implement the same counter-based generator
+    L = _lib()
+    w = _spectrum_workload(512, 192, 16, seed=91, dtype="bf16", decay=0.8)
+    x = to_device(w.x, "bf16")
+    u, v = L.loract_rsvd(x, 16, oversample=4, power_iters=0, seed=1234)
+    torch.cuda.synchronize()
+    omega_t = synth.round_to_bf16(orc.gaussian_omega_t(20, 192, 1234).astype(np.float32))
+    uo, vo = orc.rsvd(w.x.astype(np.float64), 16, oversample=4, omega_t=omega_t.astype(np.float64))
+    print(check_compress_parity(w, u, v, oracle_factors=(uo, vo)))
