@@ -28,30 +28,32 @@ HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X published fp64 vector rate
 
 
-def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: int):
+def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: int, launches: float):
     """(bound, amount per launch, unit) for a kernel name: algorithmic HBM bytes for the
-    streaming kernels, flops for the float64 small-matrix kernels."""
+    streaming kernels, flops for the float64 small-matrix kernels.  `launches` = launches of
+    that name per step (a name used by two different calls gets the mean of their amounts)."""
     fb = b                                      # factor bytes per element (= input dtype here)
-    table = {
-        # reads X once and the k sampled rows, writes Y (fp32)
-        "sketch": ("hbm", m * n * b + k * n * b + m * k * 4),
+    kp = (k + 15) // 16 * 16
+    rp = (r + 15) // 16 * 16
+    hbm = {
+        # reads X once and the k sampled rows, writes Y (fp32, possibly as split partials)
+        "sketch": m * n * b + k * n * b + m * kp * 4,
         # reads X once and U, writes V
-        "project": ("hbm", m * n * b + m * k * fb + k * n * fb),
-        "project_fused": ("hbm", m * n * b + m * k * 4 + m * k * fb + k * n * 4),
+        "project": m * n * b + m * k * fb + k * n * fb,
         # writes Xhat, reads U and V
-        "reconstruct": ("hbm", m * n * b + (m + n) * k * fb),
-        # reads dY once and B_lora, writes G (fp32)
-        "lora_dyb": ("hbm", m * n_out * b + r * n_out * b + m * r * 4),
+        "reconstruct": m * n * b + (m + n) * k * fb,
+        # reads dY once and B_lora, writes G
+        "lora_dyb": m * n_out * b + r * n_out * b + m * rp * 4,
+        # reads U and the split G, writes T
+        "lora_utg": m * k * fb + m * 2 * rp * 2 + k * 2 * rp * 4,
+        "lora_vtt": k * n * fb + n * r * 4,
     }
-    if name in table:
-        bound, amount = table[name]
-        return bound, float(amount), "GB/s"
+    if name in hbm:
+        return "hbm", float(hbm[name]), "GB/s"
     flops = {
-        "gram": 2.0 * m * k * k,
-        "apply_rinv": 2.0 * m * k * k,
-        "chol_inverse": 2.0 * k ** 3 / 3.0,
-        "lora_utg": 2.0 * m * k * r,
-        "lora_vtt": 2.0 * n * k * r,
+        "gram": 2.0 * m * kp * kp * 0.75,        # lower 64-blocks only
+        "trsm_apply": 1.0 * m * kp * kp + 2.0 * m * kp * 16,
+        "chol": kp ** 3 / 3.0,
     }
     if name in flops:
         return "alu", flops[name], "TFLOP/s"
@@ -65,6 +67,10 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-comparator", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run 5 plain device copies of X (2*|X| bytes of known traffic each) so "
+                         "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -154,7 +160,7 @@ def main() -> int:
     prof = L.loract_profile_end()
     kernels = {}
     for name, (ms, cnt) in prof.items():
-        bound, amount, unit = algorithmic_cost(name, m, n, k, b, n_out, r_l)
+        bound, amount, unit = algorithmic_cost(name, m, n, k, b, n_out, r_l, cnt / args.steps)
         avg_us = ms * 1e3 / cnt
         kernels[name] = {"avg_us": round(avg_us, 2), "launches_per_step": cnt / args.steps,
                          "share": 0.0, "bound": bound,
@@ -164,7 +170,7 @@ def main() -> int:
     for name, (ms, cnt) in prof.items():
         kernels[name]["share"] = round(ms / total_ms, 3)
     dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
-    d_bound, d_amount, d_unit = algorithmic_cost(dom, m, n, k, b, n_out, r_l)
+    d_bound, d_amount, d_unit = algorithmic_cost(dom, m, n, k, b, n_out, r_l, prof[dom][1] / args.steps)
     d_avg_s = prof[dom][0] * 1e-3 / prof[dom][1]
     if d_unit == "GB/s":
         achieved, peak = d_amount / d_avg_s / 1e9, HBM_PEAK_GBS
@@ -179,6 +185,54 @@ def main() -> int:
     roofline = {"kernel": dom, "bound": d_bound, "achieved": round(achieved, 2), "peak": peak,
                 "unit": d_unit, "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_us": round(d_avg_s * 1e6, 2), "algorithmic_per_launch": d_amount}
+
+    # the slowest HBM-streaming kernel as well (the dominant kernel may be a latency-bound one)
+    streaming = {kn: kv for kn, kv in kernels.items() if kv["bound"] == "hbm" and kv["achieved"]}
+    roofline_streaming = None
+    if streaming:
+        sn = max(streaming, key=lambda kn: prof[kn][0])
+        s_bound, s_amount, _ = algorithmic_cost(sn, m, n, k, b, n_out, r_l, prof[sn][1] / args.steps)
+        s_avg = prof[sn][0] * 1e-3 / prof[sn][1]
+        roofline_streaming = {"kernel": sn, "bound": "hbm", "achieved": round(s_amount / s_avg / 1e9, 2),
+                              "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                              "frac": round(s_amount / s_avg / 1e9 / HBM_PEAK_GBS, 4),
+                              "avg_us": round(s_avg * 1e6, 2), "algorithmic_per_launch": s_amount}
+
+    if args.pmc_calibration:
+        scratch = torch.empty_like(x)
+        for _ in range(5):
+            scratch.copy_(x)
+        torch.cuda.synchronize()
+
+    # comparator of Section 3.2 at equal rank on the same input: oversampling 8, one power iteration
+    comparator = None
+    if not args.no_comparator:
+        def rsvd():
+            L.loract_rsvd(x, k, oversample=8, power_iters=1, seed=w.seed)
+        rsteps = max(3, args.steps // 5)
+        for _ in range(2):
+            rsvd()
+        torch.cuda.synchronize()
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(rsteps):
+            rsvd()
+        e1.record()
+        torch.cuda.synchronize()
+        us_rsvd = e0.elapsed_time(e1) * 1e3 / rsteps
+        L.loract_profile_begin()
+        for _ in range(rsteps):
+            rsvd()
+        torch.cuda.synchronize()
+        rprof = L.loract_profile_end()
+        us_trunc = sum(ms for nm, (ms, cnt) in rprof.items()
+                       if nm in ("jacobi_eig", "rsvd_bbt", "rsvd_qw", "rsvd_wtb")) * 1e3 / rsteps
+        comparator = {"method": "rsvd (oversampling 8, 1 power iteration, rank %d)" % k,
+                      "total_us": round(us_rsvd, 1), "truncation_us": round(us_trunc, 1),
+                      "range_finder_us": round(us_rsvd - us_trunc, 1),
+                      "loract_compress_us": round(us_c, 1),
+                      "speedup_vs_range_finder": round((us_rsvd - us_trunc) / us_c, 2)}
 
     # accuracy of the timed outputs (cheap GPU-side figure; full parity lives in tests/)
     err = float((torch.linalg.norm(xhat.float() - x.float()) / torch.linalg.norm(x.float())).item())
@@ -200,6 +254,8 @@ def main() -> int:
                                    / ((us_c + us_r) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
         "rel_fro_err": round(err, 6),
         "roofline": roofline,
+        "roofline_streaming": roofline_streaming,
+        "comparator": comparator,
         "kernels": kernels,
     }
 
