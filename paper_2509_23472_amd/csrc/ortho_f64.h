@@ -15,6 +15,12 @@
 #include "common.h"
 
 #define OF_NB 16
+#ifndef CHOL_LDS_THREADS
+#define CHOL_LDS_THREADS 256
+#endif
+#ifndef OF_RSQ_STEPS
+#define OF_RSQ_STEPS 1
+#endif
 
 // Phase timestamps for development harnesses; compiled out in the library build.
 #ifdef OF_SKIP
@@ -156,13 +162,15 @@ __device__ inline double readlane_f64(double v, int src_lane) {
   return u.d;
 }
 
-// 1 / sqrt(x) to float64 accuracy: hardware estimate refined by two Newton steps.
+// 1 / sqrt(x) to float64 accuracy: the hardware estimate (relative error below ~2^-22) refined by
+// third-order steps y <- y (1 + e/2 + 3 e^2/8), e = 1 - x y^2, each of which cubes the error.
+template <int STEPS>
 __device__ inline double rsqrt_f64(double x) {
   double y = __builtin_amdgcn_rsq(x);
 #pragma unroll
-  for (int it = 0; it < 2; ++it) {
-    const double e = fma(-x * y, y, 1.0);           // 1 - x y^2
-    y = fma(y * fma(0.375, e, 0.5), e, y);          // y (1 + e/2 + 3 e^2 / 8)
+  for (int it = 0; it < STEPS; ++it) {
+    const double e = fma(-x * y, y, 1.0);
+    y = fma(y * fma(0.375, e, 0.5), e, y);
   }
   return y;
 }
@@ -171,9 +179,9 @@ __device__ inline double rsqrt_f64(double x) {
 // LDS mode runs 4 waves (the pivot chains are latency bound, more waves only add contention);
 // global mode runs 8 waves to overlap the memory latency of the trailing-block updates.
 template <bool LDS_MODE>
-__global__ __launch_bounds__(LDS_MODE ? 256 : 512) void chol_blocked_kernel(
+__global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocked_kernel(
     double* G, double* Dinv, int k, int kp, double tol, double shift_rel, int32_t* status) {
-  constexpr int CHOL_THREADS = LDS_MODE ? 256 : 512;
+  constexpr int CHOL_THREADS = LDS_MODE ? CHOL_LDS_THREADS : 512;
   extern __shared__ double smem[];
   // layout: gdiag[kp] | dinv[kp] | misc[8] | Pt[16][kp - 16] | (LDS mode) A[kp][kp + 2]
   double* gdiag = smem;            // original diagonal
@@ -256,7 +264,7 @@ __global__ __launch_bounds__(LDS_MODE ? 256 : 512) void chol_blocked_kernel(
     for (int j = 0; j < OF_NB; ++j) {
       const double piv = readlane_f64(a[j], j);
       const bool usable = shift > 0.0 ? (piv > 0.0) : (piv > thr[j]);
-      const double d = usable ? rsqrt_f64(piv) : 0.0;
+      const double d = usable ? rsqrt_f64<OF_RSQ_STEPS>(piv) : 0.0;
       dval[j] = d;
       any_bad = any_bad || (!usable && jb + j < k);
       a[j] *= d;
@@ -484,7 +492,7 @@ static int launch_chol_blocked(hipStream_t s, double* G, double* Dinv, int k, in
       if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(chol LDS)");
       g_chol_lds_attr_set = true;
     }
-    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(256), lds, G, Dinv, k, kp, tol,
+    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(CHOL_LDS_THREADS), lds, G, Dinv, k, kp, tol,
                   shift_rel, status);
   } else {
     const size_t lds = chol_lds_bytes(kp, false);

@@ -82,6 +82,30 @@ def test_bf16_small_and_ragged_shapes(m, n, k):
     assert u.dtype == torch.bfloat16 and v.dtype == torch.bfloat16
 
 
+@pytest.mark.parametrize("m,n,k", [(130, 64, 17), (1000, 512, 72), (4100, 1024, 136), (520, 640, 264),
+                                    (777, 320, 320), (129, 128, 128), (2048, 192, 8), (385, 448, 200)])
+def test_bf16_streaming_kernels_ragged_rows_and_all_rank_tiles(m, n, k):
+    # n % 64 == 0 selects the matrix-core streaming kernels; the shapes walk through every
+    # accumulator-tile variant (kp <= 64, <= 128, <= 256, two column blocks), the maximum rank,
+    # row counts that end inside a 128-row tile, and K ranges that do not divide evenly.
+    w = _spectrum_workload(m, n, k, seed=7 * m + n + k, dtype="bf16", decay=0.93)
+    x, u, v, xhat, status = _run(w)
+    print(check_compress_parity(w, u, v, xhat))
+
+
+def test_bf16_streaming_kernels_with_row_pitch_and_power_iteration():
+    L = _lib()
+    w = _spectrum_workload(900, 256, 40, seed=77, dtype="bf16")
+    big = torch.zeros((900, 320), dtype=torch.bfloat16, device="cuda")
+    big[:, :256] = to_device(w.x, "bf16")
+    u, v = L.loract_compress(big[:, :256], w.k, t=1, seed=w.seed)
+    out_big = torch.full((900, 384), -3.0, dtype=torch.bfloat16, device="cuda")
+    L.loract_reconstruct(u, v, out=out_big[:, :256])
+    torch.cuda.synchronize()
+    print(check_compress_parity(w, u, v, out_big[:, :256], t=1))
+    assert torch.all(out_big[:, 256:] == -3.0)
+
+
 def test_bf16_input_with_fp32_factors():
     w = _spectrum_workload(700, 256, 40, seed=9, dtype="bf16")
     x, u, v, xhat, status = _run(w, factor_dtype=torch.float32)
