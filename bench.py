@@ -60,12 +60,102 @@ def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: i
     return "hbm", 0.0, "GB/s"
 
 
+def c5_stream(args, L, torch, np) -> int:
+    """Config 5: long-context stream, 16 x 4096 tokens per site, 7 sites per decoder layer (six
+    4096-wide, one 11008-wide), rank 256.  Sites are generated on the GPU on one HIP stream
+    (harness code: X = c (G1 diag(s)) G2^T + 1e-3 N with Gaussian G1, G2 scaled to near-orthonormal
+    columns, 1024 spectrum terms, s_i = i^-1.5, per-site seed) while the previous site is compressed
+    on another stream; two X buffers alternate.  Factors of every site are kept, as in training."""
+    m, k, p = 16 * 4096, 256, 1024
+    widths = [4096] * 6 + [11008]
+    sites = [(layer, s) for layer in range(args.layers) for s in range(7)]
+    gen_stream, cmp_stream = torch.cuda.Stream(), torch.cuda.Stream()
+    xbuf = [torch.empty((m, 11008), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
+    svals = (torch.arange(1, p + 1, device="cuda", dtype=torch.float32) ** -1.5)
+    factors, errs = [], []
+    gen_done = [torch.cuda.Event() for _ in sites]
+    cmp_done = [torch.cuda.Event() for _ in sites]
+
+    def generate(i):
+        layer, s = sites[i]
+        n = widths[s]
+        g = torch.Generator(device="cuda")
+        g.manual_seed(50_000 + 7 * layer + s)
+        c = float(np.sqrt(float(m) * n) / np.linalg.norm(np.arange(1, p + 1, dtype=np.float64) ** -1.5))
+        g1 = torch.randn((m, p), generator=g, device="cuda", dtype=torch.float32) * (c / np.sqrt(m))
+        g2 = torch.randn((n, p), generator=g, device="cuda", dtype=torch.float32) / np.sqrt(n)
+        x = xbuf[i % 2].view(-1)[: m * n].view(m, n)
+        sig = ((g1 * svals).to(torch.bfloat16) @ g2.to(torch.bfloat16).t()).float()
+        sig.add_(torch.randn((m, n), generator=g, device="cuda", dtype=torch.float32), alpha=1e-3)
+        x.copy_(sig)
+        return x
+
+    def run(check):
+        factors.clear()
+        errs.clear()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        views = [None, None]
+        for i in range(len(sites) + 1):
+            if i < len(sites):
+                with torch.cuda.stream(gen_stream):
+                    if i >= 2:
+                        gen_stream.wait_event(cmp_done[i - 2])      # buffer i % 2 is free again
+                    views[i % 2] = generate(i)
+                    gen_done[i].record(gen_stream)
+            j = i - 1
+            if j >= 0:
+                with torch.cuda.stream(cmp_stream):
+                    cmp_stream.wait_event(gen_done[j])
+                    x = views[j % 2]
+                    u, v = L.loract_compress(x, k, seed=50_000 + j)
+                    if check:
+                        xh = L.loract_reconstruct(u, v)
+                        errs.append(torch.linalg.norm(xh.float() - x.float()) / torch.linalg.norm(x.float()))
+                        del xh
+                    cmp_done[j].record(cmp_stream)
+                    factors.append((u, v))
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    run(False)                                    # warm-up (allocations, first-use set-up)
+    seconds = run(False)
+    run(True)
+    total_bytes = sum(m * widths[s] * 2 for _, s in sites)
+    # compress-only time of the same sites, back to back on one stream, inputs resident
+    x4096 = xbuf[0].view(-1)[: m * 4096].view(m, 4096)
+    x11008 = xbuf[1].view(-1)[: m * 11008].view(m, 11008)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _, s in sites:
+        L.loract_compress(x11008 if s == 6 else x4096, k, seed=1)
+    torch.cuda.synchronize()
+    compress_only = time.perf_counter() - t0
+    out = {
+        "metric": "activation GB/s compressed (long-context stream, generation overlapped)",
+        "value": round(total_bytes / seconds / 1e9, 2), "unit": "GB/s", "n_gpus": 1,
+        "steps": len(sites), "warmup": len(sites), "ms_per_step": round(seconds * 1e3 / len(sites), 3),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "c5stream: %d layers x 7 sites of 65536 x {4096 x6, 11008 x1} bf16, rank 256, "
+                               "two HIP streams (generate || compress), double-buffered X" % args.layers},
+        "compress_only_gbps": round(total_bytes / compress_only / 1e9, 2),
+        "compress_only_ms_per_site": round(compress_only * 1e3 / len(sites), 3),
+        "rel_fro_err_min_max": [round(float(min(errs)), 5), round(float(max(errs)), 5)],
+        "factor_bytes_kept": int(sum(u.numel() * 2 + v.numel() * 2 for u, v in factors)),
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4"])
+    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "c5stream"])
+    ap.add_argument("--layers", type=int, default=2,
+                    help="c5stream only: decoder layers to stream (7 sites each; the full config is 32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparator", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -89,6 +179,8 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
 
+    if args.workload == "c5stream":
+        return c5_stream(args, L, torch, np)
     if args.workload == "c3":
         w = synth.c3_llama()
     else:
@@ -198,6 +290,37 @@ def main() -> int:
                               "frac": round(s_amount / s_avg / 1e9 / HBM_PEAK_GBS, 4),
                               "avg_us": round(s_avg * 1e6, 2), "algorithmic_per_launch": s_amount}
 
+    # several independent sites in flight on separate HIP streams (as the sites of a layer are in
+    # training): the latency-bound single-workgroup kernels of one site overlap the streaming
+    # kernels of the others
+    pipelined = None
+    if not args.no_comparator:
+        nstreams = 3
+        streams = [torch.cuda.Stream() for _ in range(nstreams)]
+        held = []
+        for _ in range(nstreams):
+            held.append((x.clone(), torch.empty_like(u), torch.empty_like(v), torch.empty_like(xhat),
+                         torch.empty_like(ga)))
+
+        def round_of_sites():
+            for st, (xs, us, vs, xh, gs) in zip(streams, held):
+                with torch.cuda.stream(st):
+                    L.loract_compress(xs, k, seed=w.seed, out=(us, vs))
+                    L.loract_reconstruct(us, vs, out=xh)
+                    L.loract_lora_grad(us, vs, dy, bl, scale=1.0, out=gs)
+
+        for _ in range(3):
+            round_of_sites()
+        torch.cuda.synchronize()
+        tp0 = time.perf_counter()
+        for _ in range(args.steps):
+            round_of_sites()
+        torch.cuda.synchronize()
+        us_site = (time.perf_counter() - tp0) * 1e6 / (args.steps * nstreams)
+        same = all(torch.equal(h[1], u) and torch.equal(h[3], xhat) for h in held)
+        pipelined = {"streams": nstreams, "us_per_site": round(us_site, 1),
+                     "gbps": round(x_bytes / us_site / 1e3, 1), "bit_identical_to_single_stream": bool(same)}
+
     if args.pmc_calibration:
         scratch = torch.empty_like(x)
         for _ in range(5):
@@ -256,6 +379,7 @@ def main() -> int:
         "roofline": roofline,
         "roofline_streaming": roofline_streaming,
         "comparator": comparator,
+        "pipelined": pipelined,
         "kernels": kernels,
     }
 

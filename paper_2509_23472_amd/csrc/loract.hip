@@ -89,7 +89,7 @@ struct Plan {
   int kp;                // l rounded up to a multiple of 16 (column count of the fp32 work buffers)
   int gram_splits, proj_splits;
   size_t off_idx, off_a, off_b, off_ub, off_g, off_rinv, off_dpart, off_fpart, off_zt;
-  size_t off_bmat, off_eig, off_omega, off_dinv;
+  size_t off_bmat, off_eig, off_omega, off_dinv, off_q1b, off_nsT, off_gbak, off_flag;
   int sketch_splits, bgram_splits;
   size_t total;
 };
@@ -138,6 +138,10 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_g = take((size_t)pl->kp * pl->kp * 8);
   pl->off_rinv = take((size_t)l * l * 8);
   pl->off_dinv = take((size_t)pl->kp * 16 * 8);
+  pl->off_q1b = take(pl->bf16_path ? (size_t)m * pl->kp * 2 : 0);
+  pl->off_nsT = take(pl->bf16_path ? (size_t)pl->kp * pl->kp * 2 : 0);
+  pl->off_gbak = take(pl->bf16_path && pl->kp > 128 ? (size_t)pl->kp * pl->kp * 8 : 0);
+  pl->off_flag = take(256);
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
@@ -193,7 +197,7 @@ static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows
       a.X = (const bf16_t*)c.X; a.ldx = c.p->ldx; a.m = m; a.n = n;
       a.B = (const bf16_t*)Bt; a.ldb = ldb; a.b_rows = rows; a.l = l; a.kp = c.pl.kp;
       a.Y = (float*)Y; a.part = ws_ptr<float>(c, c.pl.off_fpart); a.splits = c.pl.sketch_splits;
-      a.k_per_split = 0;
+      a.k_per_split = 0; a.run_flag = nullptr;
       return launch_sketch_mfma(c.s, a);
     }
     return launch_gemm_bf16("sketch_generic", c.s, (const bf16_t*)c.X, c.p->ldx, 1, (const bf16_t*)Bt,
@@ -240,20 +244,43 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   double* G = ws_ptr<double>(c, c.pl.off_g);
   double* Dinv = ws_ptr<double>(c, c.pl.off_dinv);
   double* part = ws_ptr<double>(c, c.pl.off_dpart);
-  const double shift_rel = 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16;
+  double* Gbak = kp > 128 ? ws_ptr<double>(c, c.pl.off_gbak) : nullptr;
+  bf16_t* Q1b = ws_ptr<bf16_t>(c, c.pl.off_q1b);
+  bf16_t* nsT = ws_ptr<bf16_t>(c, c.pl.off_nsT);
+  int32_t* ns_flag = ws_ptr<int32_t>(c, c.pl.off_flag);
+  // the Newton-Schulz finish reuses the sketch kernel, which wants a K extent that is a multiple of 64
+  const bool ns_ok = (kp % 64 == 0);
+  CholArgs ch;
+  ch.G = G; ch.G_backup = Gbak; ch.Dinv = Dinv; ch.k = l; ch.kp = kp; ch.tol = 0.0; ch.status = c.status;
+  ch.shift_rel = 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16;
+  ch.unshifted_thresh = chol_unshifted_thresh(l);
+  ch.ns_T = nullptr; ch.ns_flag = nullptr; ch.ns_tol = 0.0;
   TrsmArgs t;
   t.L = G; t.Dinv = Dinv; t.m = m; t.kp = kp; t.k = l;
-  // round 1
-  LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, part, G));
-  LORACT_TRY(launch_chol_blocked(c.s, G, Dinv, l, kp, shift_rel, c.status));
+  // round 1: Q1 = Y R^{-1} (fp32, plus a bf16 copy for a possible Newton-Schulz finish)
+  LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, part, G, Gbak));
+  ch.round = 1;
+  LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = Y; t.ldy = kp; t.Q = tmp; t.ldq = kp; t.out_ek = EK_F32; t.out_cols = kp;
-  t.Qb = nullptr; t.ldqb = 0;
+  t.Qb = ns_ok ? Q1b : nullptr; t.ldqb = kp; t.skip_flag = nullptr;
   LORACT_TRY(launch_trsm_apply(c.s, t));
-  // round 2
-  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, part, G));
-  LORACT_TRY(launch_chol_blocked(c.s, G, Dinv, l, kp, 0.0, c.status));
+  // round 2: either Q = Q1 (I - E/2) when E = Q1^T Q1 - I is small, or a second Cholesky QR
+  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, part, G, nullptr));
+  ch.round = 2;
+  if (ns_ok) { ch.ns_T = nsT; ch.ns_flag = ns_flag; ch.ns_tol = 0.015; }
+  LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = tmp; t.Q = Q; t.ldq = l; t.out_ek = q_ek; t.out_cols = l; t.Qb = Qb; t.ldqb = l;
-  return launch_trsm_apply(c.s, t);
+  t.skip_flag = ns_ok ? ns_flag : nullptr;
+  LORACT_TRY(launch_trsm_apply(c.s, t));
+  if (!ns_ok) return LORACT_OK;
+  SketchArgs a;                       // C = Q1b T^T  (T symmetric), into the free sketch buffer
+  a.X = Q1b; a.ldx = kp; a.m = m; a.n = kp; a.B = nsT; a.ldb = kp; a.b_rows = nullptr; a.l = kp; a.kp = kp;
+  a.Y = (float*)Y; a.part = nullptr; a.splits = 1; a.k_per_split = 0; a.run_flag = ns_flag;
+  LORACT_TRY(launch_sketch_mfma(c.s, a, "ns_correct"));
+  const int blocks = (int)std::min<int64_t>(ceil_div64(m * (kp / 4), 256), 2048);
+  LORACT_LAUNCH("ns_finalize", c.s, ns_finalize_kernel, dim3(blocks), dim3(256), 0, (const float*)tmp,
+                (const float*)Y, m, kp, l, Q, q_ek, Qb, (const int32_t*)ns_flag);
+  return LORACT_OK;
 }
 
 // Bt (l x n) = Q^T X: step 8 of Algorithm 1 (and the first half of step 5).
@@ -481,7 +508,7 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
     a.X = (const bf16_t*)dY_dev; a.ldx = n_out; a.m = m; a.n = n_out;
     a.B = (const bf16_t*)Blora_dev; a.ldb = n_out; a.b_rows = nullptr; a.l = r_lora; a.kp = rp;
     a.Y = (float*)(ws + lp.off_g); a.part = (float*)(ws + lp.off_gpart); a.splits = lp.g_splits;
-    a.k_per_split = 0;
+    a.k_per_split = 0; a.run_flag = nullptr;
     bf16_t* Gsplit = (bf16_t*)(ws + lp.off_gsplit);
     LORACT_TRY(launch_sketch_mfma(s, a, "lora_dyb", Gsplit));
     // [T_hi | T_lo] = U^T [G_hi | G_lo]  (k x 2rp)

@@ -116,7 +116,8 @@ __global__ __launch_bounds__(256) void gram_mfma_kernel(GramArgs g) {
 
 // G[i][j] (lower triangle, kp x kp) = sum over chunks, ascending.  One thread per element.
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, int chunks,
-                                                          int nblocks, int kp, double* G) {
+                                                          int nblocks, int kp, double* G,
+                                                          double* G_copy) {
   const int b = blockIdx.y;
   int bi, bj;
   gram_block_of(b, &bi, &bj);
@@ -136,6 +137,7 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, in
   }
   for (; c < chunks; ++c) s += src[(int64_t)c * stride];
   G[(int64_t)i * kp + j] = s;
+  if (G_copy) G_copy[(int64_t)i * kp + j] = s;
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -178,10 +180,40 @@ __device__ inline double rsqrt_f64(double x) {
 
 // LDS mode runs 4 waves (the pivot chains are latency bound, more waves only add contention);
 // global mode runs 8 waves to overlap the memory latency of the trailing-block updates.
+//
+// round == 1 (Gram matrix of the sketch): the factorisation is first attempted WITHOUT a shift;
+//   a pivot that is not above unshifted_thresh * G[j][j] (a small multiple of the rounding level
+//   k u) abandons the attempt and the matrix is factored again as G + s I, s = shift_rel * trace
+//   (restored from G itself in LDS mode, from G_backup in global mode).  Unshifted factors leave
+//   Q1 = Y R^{-1} orthonormal to ~u cond(G); shifted ones only well conditioned (see chol.h).
+// round == 2 (Gram matrix of Q1): if ns_flag is given, E = G - I is measured first.  When
+//   ||E||_F <= ns_tol the factorisation is skipped: T = -E/2 is written to ns_T (bf16, kp x kp)
+//   and *ns_flag = 1, so that the caller finishes with the first-order Newton-Schulz correction
+//   Q = Q1 (I - E/2), whose defect is ~ (3/4) ||E||^2.  Otherwise *ns_flag = 0 and the matrix is
+//   factored unshifted with the clamping rule of chol.h.
+struct CholArgs {
+  double* G;
+  const double* G_backup;
+  double* Dinv;
+  int k, kp;
+  int round;
+  double tol;               // round 2 clamping level
+  double shift_rel;         // round 1 shift (second attempt)
+  double unshifted_thresh;  // round 1 breakdown level of the unshifted attempt (0 = always shift)
+  int32_t* status;
+  bf16_t* ns_T;
+  int32_t* ns_flag;
+  double ns_tol;
+};
+
 template <bool LDS_MODE>
-__global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocked_kernel(
-    double* G, double* Dinv, int k, int kp, double tol, double shift_rel, int32_t* status) {
+__global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocked_kernel(CholArgs g) {
   constexpr int CHOL_THREADS = LDS_MODE ? CHOL_LDS_THREADS : 512;
+  double* const G = g.G;
+  double* const Dinv = g.Dinv;
+  const int k = g.k, kp = g.kp;
+  const double tol = g.tol;
+  int32_t* const status = g.status;
   extern __shared__ double smem[];
   // layout: gdiag[kp] | dinv[kp] | misc[8] | Pt[16][kp - 16] | (LDS mode) A[kp][kp + 2]
   double* gdiag = smem;            // original diagonal
@@ -191,7 +223,8 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   double* Pt = smem + 2 * kp + 8;  // panel below the diagonal block, transposed: Pt[p][row - below]
   double* Am = LDS_MODE ? (Pt + OF_NB * ptld) : G;
   const int lda = LDS_MODE ? kp + 1 : kp;   // odd pitch: column walks hit distinct banks
-  __shared__ int deficient;
+  __shared__ int deficient, restart;
+  __shared__ double red_e[16];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   OF_STAMP(0);
@@ -210,19 +243,74 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
     }
   }
   for (int i = t; i < kp; i += CHOL_THREADS) gdiag[i] = G[(int64_t)i * kp + i];
-  if (t == 0) deficient = 0;
+  if (t == 0) { deficient = 0; restart = 0; }
   __syncthreads();
   OF_STAMP(1);
+
+  // ---- round 2: is Q1 already orthonormal enough for a Newton-Schulz finish?
+  if (g.round == 2 && g.ns_flag) {
+    // only the lower 64 x 64 blocks of G are defined; an off-diagonal block stands for its mirror too
+    double e2 = 0.0;
+    for (int e = t; e < k * k; e += CHOL_THREADS) {
+      const int i = e / k, j = e - i * k;
+      if ((i >> 6) < (j >> 6)) continue;
+      const double v = (LDS_MODE ? Am[i * lda + j] : G[(int64_t)i * kp + j]) - (i == j ? 1.0 : 0.0);
+      e2 += ((i >> 6) == (j >> 6)) ? v * v : 2.0 * v * v;
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) e2 += __shfl_xor(e2, off);
+    if (lane == 0) red_e[wave] = e2;
+    __syncthreads();
+    double tot = 0.0;
+    for (int w = 0; w < CHOL_THREADS / 64; ++w) tot += red_e[w];
+    if (tot <= g.ns_tol * g.ns_tol) {       // also false for NaN
+      for (int e = t; e < kp * kp; e += CHOL_THREADS) {
+        const int i = e / kp, j = e - i * kp;
+        double v = 0.0;
+        if (i < k && j < k) {
+          const int a = ((i >> 6) >= (j >> 6)) ? i : j, b = ((i >> 6) >= (j >> 6)) ? j : i;
+          v = -0.5 * ((LDS_MODE ? Am[a * lda + b] : G[(int64_t)a * kp + b]) - (i == j ? 1.0 : 0.0));
+        }
+        g.ns_T[e] = (bf16_t)(float)v;
+      }
+      if (t == 0) *g.ns_flag = 1;
+      return;
+    }
+    if (t == 0) *g.ns_flag = 0;
+  }
+
+  double trace_sum = 0.0;
   if (wave == 0) {
     double tr = 0.0;
     for (int i = lane; i < kp; i += 64) tr += gdiag[i];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) tr += __shfl_xor(tr, off);
-    if (lane == 0) misc[0] = shift_rel * tr;
+    if (lane == 0) misc[0] = tr;
   }
   __syncthreads();
-  const double shift = misc[0];
+  trace_sum = misc[0];
   OF_STAMP(2);
+
+  const bool try_unshifted = g.round == 1 && g.unshifted_thresh > 0.0;
+  for (int attempt = try_unshifted ? 0 : 1; attempt < 2; ++attempt) {
+  const bool unshifted_attempt = g.round == 1 && attempt == 0;
+  const double shift = (g.round == 1 && attempt == 1) ? g.shift_rel * trace_sum : 0.0;
+  if (attempt == 1 && try_unshifted) {
+    // the unshifted attempt broke down: restore the matrix and start over with the shift
+    if (LDS_MODE) {
+      const int half = kp >> 1;
+      for (int e = t; e < kp * half; e += CHOL_THREADS) {
+        const int i = e / half, j2 = e - i * half;
+        const double2 v = *(const double2*)(G + (int64_t)i * kp + 2 * j2);
+        Am[i * lda + 2 * j2] = v.x;
+        Am[i * lda + 2 * j2 + 1] = v.y;
+      }
+    } else {
+      for (int e = t; e < kp * kp; e += CHOL_THREADS) G[e] = g.G_backup[e];
+    }
+    if (t == 0) restart = 0;
+    __syncthreads();
+  }
 
   for (int jb = 0; jb < kp; jb += OF_NB) {
 #ifdef OF_TIMING
@@ -237,14 +325,15 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
     constexpr int NWAVES = CHOL_THREADS / 64;
     const int npass = nrows_below > 0 ? (nrows_below + 48 * NWAVES - 1) / (48 * NWAVES) : 1;
     double dsave[OF_NB];
-    double thr[OF_NB];
+    double thr[OF_NB], gdiag_reg[OF_NB];
 #pragma unroll
     for (int c = 0; c < OF_NB; ++c) {
       double v = 0.0;
       if (lane < 16 && c <= lane) v = Am[(jb + lane) * lda + jb + c];
       if (lane < 16 && c == lane) v += shift;
       dsave[c] = v;
-      thr[c] = tol * gdiag[jb + c];
+      gdiag_reg[c] = gdiag[jb + c];
+      thr[c] = tol * gdiag_reg[c];
     }
     __syncthreads();   // every wave has read the unfactored diagonal block
     for (int pass = 0; pass < npass; ++pass) {
@@ -263,10 +352,14 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
 #pragma unroll
     for (int j = 0; j < OF_NB; ++j) {
       const double piv = readlane_f64(a[j], j);
-      const bool usable = shift > 0.0 ? (piv > 0.0) : (piv > thr[j]);
-      const double d = usable ? rsqrt_f64<OF_RSQ_STEPS>(piv) : 0.0;
+      const bool live = jb + j < k;                      // padding columns never count
+      bool usable;
+      if (unshifted_attempt) usable = piv > g.unshifted_thresh * gdiag_reg[j];
+      else if (g.round == 1) usable = piv > 0.0;
+      else usable = piv > thr[j];
+      const double d = (usable && live) ? rsqrt_f64<OF_RSQ_STEPS>(piv) : 0.0;
       dval[j] = d;
-      any_bad = any_bad || (!usable && jb + j < k);
+      any_bad = any_bad || (!usable && live);
       a[j] *= d;
 #pragma unroll
       for (int c = j + 1; c < OF_NB; ++c) {
@@ -292,11 +385,14 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
       if (lane == 0) {
 #pragma unroll
         for (int j = 0; j < OF_NB; ++j) dinv[jb + j] = dval[j];
-        if (any_bad) deficient = 1;
+        if (any_bad) {
+          if (unshifted_attempt) restart = 1; else deficient = 1;
+        }
       }
     }
     }
     __syncthreads();
+    if (restart) break;          // uniform: written before the barrier
 #ifdef OF_TIMING
     { long long now = wall_clock64(); t_ps += now - t_m2; t_panel += now - t_mark; t_mark = now; }
 #endif
@@ -331,6 +427,9 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
 #ifdef OF_TIMING
     t_trail += wall_clock64() - t_mark;
 #endif
+  }
+  if (!restart) break;
+  __syncthreads();
   }
   OF_STAMP(3);
 #ifdef OF_TIMING
@@ -394,10 +493,12 @@ struct TrsmArgs {
   int out_cols;         // number of columns to write (kp or k)
   bf16_t* Qb;           // optional second bf16 copy (ld = ldqb, out_cols columns), may be null
   int64_t ldqb;
+  const int32_t* skip_flag;   // optional: the launch does nothing when *skip_flag != 0
 };
 
 template <int NJ>
 __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
+  if (g.skip_flag && *g.skip_flag != 0) return;
   const int lane = threadIdx.x;
   const int lc = lane & 15, lr = lane >> 4;
   const int64_t row = (int64_t)blockIdx.x * 16 + lc;
@@ -437,6 +538,34 @@ __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Newton-Schulz finish: Q = Q1 + C with C = Q1 (-E/2) (computed by the bf16 matrix-core product
+// of the sketch kernel from the bf16 copy of Q1; the correction is O(||E||) small, so bf16 inputs
+// cost nothing at the accuracy required).  Runs only when *flag != 0.
+__global__ __launch_bounds__(256) void ns_finalize_kernel(const float* Q1, const float* C,
+                                                          int64_t m, int kp, int l, void* Q,
+                                                          int q_ek, bf16_t* Qb,
+                                                          const int32_t* flag) {
+  if (*flag == 0) return;
+  const int c4 = kp >> 2;
+  const int64_t total = m * c4;
+  for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
+    const int64_t r = e / c4;
+    const int c = (int)(e - r * c4) << 2;
+    const f32x4 a = *(const f32x4*)(Q1 + r * kp + c);
+    const f32x4 b = *(const f32x4*)(C + r * kp + c);
+    const f32x4 q = a + b;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      if (c + u < l) {
+        if (q_ek == EK_F32) ((float*)Q)[r * l + c + u] = q[u];
+        else ((bf16_t*)Q)[r * l + c + u] = (bf16_t)q[u];
+        if (Qb) Qb[r * l + c + u] = (bf16_t)q[u];
+      }
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------------------------
 // Host-side launchers.
 
 static int gram_rows_per_chunk(int64_t m, int nblocks) {
@@ -458,7 +587,7 @@ static size_t gram_partial_bytes(int64_t m, int kp) {
 }
 
 static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t m, int kp,
-                            double* part, double* G) {
+                            double* part, double* G, double* G_copy = nullptr) {
   GramArgs g;
   g.Y = Y; g.ldy = ldy; g.m = m; g.kp = kp;
   g.nb64 = (kp + 63) / 64;
@@ -468,7 +597,7 @@ static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t 
   const int chunks = (int)ceil_div64(m, g.rows_per_chunk);
   LORACT_LAUNCH("gram", s, gram_mfma_kernel, dim3(chunks, nblocks), dim3(256), 0, g);
   LORACT_LAUNCH("gram_reduce", s, gram_reduce_kernel, dim3(16, nblocks), dim3(256), 0,
-                (const double*)part, chunks, nblocks, kp, G);
+                (const double*)part, chunks, nblocks, kp, G, G_copy);
   return LORACT_OK;
 }
 
@@ -481,23 +610,25 @@ static size_t chol_lds_bytes(int kp, bool lds_mode) {
   return doubles * sizeof(double);
 }
 
-static int launch_chol_blocked(hipStream_t s, double* G, double* Dinv, int k, int kp,
-                               double shift_rel, int32_t* status) {
-  const double tol = ((double)k * 5.9604644775390625e-08) * ((double)k * 5.9604644775390625e-08);
-  if (kp <= 128) {
-    const size_t lds = chol_lds_bytes(kp, true);
+// Breakdown level of the unshifted first-round attempt: 16 k u (pivots below it are within a
+// couple of digits of the rounding noise of the factorisation).
+static inline double chol_unshifted_thresh(int k) { return 16.0 * (double)k * 1.1102230246251565e-16; }
+
+static int launch_chol_blocked(hipStream_t s, CholArgs a) {
+  a.tol = ((double)a.k * 5.9604644775390625e-08) * ((double)a.k * 5.9604644775390625e-08);
+  if (a.kp <= 128) {
+    const size_t lds = chol_lds_bytes(a.kp, true);
     if (lds > 64 * 1024 && !g_chol_lds_attr_set) {
       hipError_t e = hipFuncSetAttribute((const void*)chol_blocked_kernel<true>,
                                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
       if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(chol LDS)");
       g_chol_lds_attr_set = true;
     }
-    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(CHOL_LDS_THREADS), lds, G, Dinv, k, kp, tol,
-                  shift_rel, status);
+    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(CHOL_LDS_THREADS), lds, a);
   } else {
-    const size_t lds = chol_lds_bytes(kp, false);
-    LORACT_LAUNCH("chol", s, chol_blocked_kernel<false>, dim3(1), dim3(512), lds, G, Dinv, k, kp,
-                  tol, shift_rel, status);
+    if (a.round == 1 && a.unshifted_thresh > 0.0 && !a.G_backup) return LORACT_ERR_INVALID_ARG;
+    const size_t lds = chol_lds_bytes(a.kp, false);
+    LORACT_LAUNCH("chol", s, chol_blocked_kernel<false>, dim3(1), dim3(512), lds, a);
   }
   return LORACT_OK;
 }

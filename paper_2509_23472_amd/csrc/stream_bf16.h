@@ -115,6 +115,7 @@ struct SketchArgs {
   float* part;           // [splits][m][kp], used when splits > 1
   int splits;
   int64_t k_per_split;   // multiple of SB_BK
+  const int32_t* run_flag;   // optional: the launch does nothing when *run_flag == 0
 };
 
 template <int NT, int STAGES>
@@ -123,6 +124,7 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
   constexpr int A_BYTES = SB_BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int LOADS = 4 + 2 * NT;     // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
+  if (g.run_flag && *g.run_flag == 0) return;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
