@@ -141,7 +141,7 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_q1b = take(pl->bf16_path ? (size_t)m * pl->kp * 2 : 0);
   pl->off_nsT = take(pl->bf16_path ? (size_t)pl->kp * pl->kp * 2 : 0);
   pl->off_gbak = take(pl->bf16_path && pl->kp > 128 ? (size_t)pl->kp * pl->kp * 8 : 0);
-  pl->off_flag = take(256);
+  pl->off_flag = take(64 + 8 * 16 * 16);   // flag word, then up to 16 x 15 shares of ||E||^2
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
@@ -254,20 +254,22 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   ch.G = G; ch.G_backup = Gbak; ch.Dinv = Dinv; ch.k = l; ch.kp = kp; ch.tol = 0.0; ch.status = c.status;
   ch.shift_rel = 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16;
   ch.unshifted_thresh = chol_unshifted_thresh(l);
-  ch.ns_T = nullptr; ch.ns_flag = nullptr; ch.ns_tol = 0.0;
+  ch.ns_e2 = nullptr; ch.ns_e2_count = 0; ch.ns_flag = nullptr; ch.ns_tol = 0.0;
   TrsmArgs t;
   t.L = G; t.Dinv = Dinv; t.m = m; t.kp = kp; t.k = l;
   // round 1: Q1 = Y R^{-1} (fp32, plus a bf16 copy for a possible Newton-Schulz finish)
-  LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, part, G, Gbak));
+  LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, l, part, G, Gbak));
   ch.round = 1;
   LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = Y; t.ldy = kp; t.Q = tmp; t.ldq = kp; t.out_ek = EK_F32; t.out_cols = kp;
   t.Qb = ns_ok ? Q1b : nullptr; t.ldqb = kp; t.skip_flag = nullptr;
   LORACT_TRY(launch_trsm_apply(c.s, t));
   // round 2: either Q = Q1 (I - E/2) when E = Q1^T Q1 - I is small, or a second Cholesky QR
-  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, part, G, nullptr));
+  double* ns_e2 = ws_ptr<double>(c, c.pl.off_flag) + 8;      // after the flag word
+  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr,
+                              ns_ok ? ns_e2 : nullptr));
   ch.round = 2;
-  if (ns_ok) { ch.ns_T = nsT; ch.ns_flag = ns_flag; ch.ns_tol = 0.015; }
+  if (ns_ok) { ch.ns_e2 = ns_e2; ch.ns_e2_count = 16 * gram_nblocks(kp); ch.ns_flag = ns_flag; ch.ns_tol = 0.015; }
   LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = tmp; t.Q = Q; t.ldq = l; t.out_ek = q_ek; t.out_cols = l; t.Qb = Qb; t.ldqb = l;
   t.skip_flag = ns_ok ? ns_flag : nullptr;

@@ -15,6 +15,9 @@
 #include "common.h"
 
 #define OF_NB 16
+#ifndef GRAM_TARGET_WGS
+#define GRAM_TARGET_WGS 384
+#endif
 #ifndef CHOL_LDS_THREADS
 #define CHOL_LDS_THREADS 256
 #endif
@@ -115,29 +118,52 @@ __global__ __launch_bounds__(256) void gram_mfma_kernel(GramArgs g) {
 }
 
 // G[i][j] (lower triangle, kp x kp) = sum over chunks, ascending.  One thread per element.
+// Optional by-products for the second round (ns_T != null): with E = G - I restricted to the
+// live k x k part, T = -E/2 as a full symmetric bf16 matrix (pad rows/columns zero), and this
+// workgroup's share of ||E||_F^2 in ns_e2[workgroup] (an off-diagonal block counts twice, for its
+// mirror image).  The consumer adds the shares in index order.
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, int chunks,
-                                                          int nblocks, int kp, double* G,
-                                                          double* G_copy) {
+                                                          int nblocks, int kp, int k, double* G,
+                                                          double* G_copy, bf16_t* ns_T,
+                                                          double* ns_e2) {
+  __shared__ double red[4];
   const int b = blockIdx.y;
   int bi, bj;
   gram_block_of(b, &bi, &bj);
   const int e = blockIdx.x * 256 + threadIdx.x;     // gridDim.x = 16
   const int i = bi * 64 + (e >> 6), j = bj * 64 + (e & 63);
-  if (i >= kp || j >= kp) return;
-  const double* src = part + (int64_t)b * 4096 + e;
-  const int64_t stride = (int64_t)nblocks * 4096;
-  double s = 0.0;
-  int c = 0;
-  for (; c + 8 <= chunks; c += 8) {
-    double v[8];
+  double contrib = 0.0;
+  if (i < kp && j < kp) {
+    const double* src = part + (int64_t)b * 4096 + e;
+    const int64_t stride = (int64_t)nblocks * 4096;
+    double s = 0.0;
+    int c = 0;
+    for (; c + 8 <= chunks; c += 8) {
+      double v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(c + u) * stride];
+      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(c + u) * stride];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) s += v[u];
+      for (int u = 0; u < 8; ++u) s += v[u];
+    }
+    for (; c < chunks; ++c) s += src[(int64_t)c * stride];
+    G[(int64_t)i * kp + j] = s;
+    if (G_copy) G_copy[(int64_t)i * kp + j] = s;
+    if (ns_T) {
+      double ev = 0.0;
+      if (i < k && j < k) ev = s - (i == j ? 1.0 : 0.0);
+      const bf16_t tv = (bf16_t)(float)(-0.5 * ev);
+      ns_T[(int64_t)i * kp + j] = tv;
+      if (bi != bj) ns_T[(int64_t)j * kp + i] = tv;
+      contrib = (bi == bj) ? ev * ev : 2.0 * ev * ev;
+    }
   }
-  for (; c < chunks; ++c) s += src[(int64_t)c * stride];
-  G[(int64_t)i * kp + j] = s;
-  if (G_copy) G_copy[(int64_t)i * kp + j] = s;
+  if (ns_T) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) contrib += __shfl_xor(contrib, off);
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = contrib;
+    __syncthreads();
+    if (threadIdx.x == 0) ns_e2[blockIdx.y * gridDim.x + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+  }
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -187,8 +213,8 @@ __device__ inline double rsqrt_f64(double x) {
 //   (restored from G itself in LDS mode, from G_backup in global mode).  Unshifted factors leave
 //   Q1 = Y R^{-1} orthonormal to ~u cond(G); shifted ones only well conditioned (see chol.h).
 // round == 2 (Gram matrix of Q1): if ns_flag is given, E = G - I is measured first.  When
-//   ||E||_F <= ns_tol the factorisation is skipped: T = -E/2 is written to ns_T (bf16, kp x kp)
-//   and *ns_flag = 1, so that the caller finishes with the first-order Newton-Schulz correction
+//   ||E||_F <= ns_tol the factorisation is skipped (T = -E/2 was already written by
+//   gram_reduce_kernel) and *ns_flag = 1, so that the caller finishes with the first-order Newton-Schulz correction
 //   Q = Q1 (I - E/2), whose defect is ~ (3/4) ||E||^2.  Otherwise *ns_flag = 0 and the matrix is
 //   factored unshifted with the clamping rule of chol.h.
 struct CholArgs {
@@ -201,7 +227,8 @@ struct CholArgs {
   double shift_rel;         // round 1 shift (second attempt)
   double unshifted_thresh;  // round 1 breakdown level of the unshifted attempt (0 = always shift)
   int32_t* status;
-  bf16_t* ns_T;
+  const double* ns_e2;      // round 2: shares of ||E||_F^2 from gram_reduce_kernel
+  int ns_e2_count;
   int32_t* ns_flag;
   double ns_tol;
 };
@@ -224,13 +251,27 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   double* Am = LDS_MODE ? (Pt + OF_NB * ptld) : G;
   const int lda = LDS_MODE ? kp + 1 : kp;   // odd pitch: column walks hit distinct banks
   __shared__ int deficient, restart;
-  __shared__ double red_e[16];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   OF_STAMP(0);
 #ifdef OF_TIMING
   long long t_panel = 0, t_trail = 0, t_mark = 0, t_pl = 0, t_pc = 0, t_ps = 0, t_m2 = 0;
 #endif
+  if (t == 0) { deficient = 0; restart = 0; }
+  __syncthreads();
+
+  // ---- round 2: is Q1 already orthonormal enough for a Newton-Schulz finish?  gram_reduce_kernel
+  // has left ||E||_F^2 in pieces (and T = -E/2); on this branch the kernel ends here.
+  if (g.round == 2 && g.ns_flag) {
+    double tot = 0.0;
+    for (int w = 0; w < g.ns_e2_count; ++w) tot += g.ns_e2[w];     // same order in every thread
+    if (tot <= g.ns_tol * g.ns_tol) {       // also false for NaN
+      if (t == 0) *g.ns_flag = 1;
+      return;
+    }
+    if (t == 0) *g.ns_flag = 0;
+  }
+
   if (LDS_MODE) {
     // kp is a multiple of 16: copy whole rows two doubles at a time
     const int half = kp >> 1;
@@ -243,41 +284,8 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
     }
   }
   for (int i = t; i < kp; i += CHOL_THREADS) gdiag[i] = G[(int64_t)i * kp + i];
-  if (t == 0) { deficient = 0; restart = 0; }
   __syncthreads();
   OF_STAMP(1);
-
-  // ---- round 2: is Q1 already orthonormal enough for a Newton-Schulz finish?
-  if (g.round == 2 && g.ns_flag) {
-    // only the lower 64 x 64 blocks of G are defined; an off-diagonal block stands for its mirror too
-    double e2 = 0.0;
-    for (int e = t; e < k * k; e += CHOL_THREADS) {
-      const int i = e / k, j = e - i * k;
-      if ((i >> 6) < (j >> 6)) continue;
-      const double v = (LDS_MODE ? Am[i * lda + j] : G[(int64_t)i * kp + j]) - (i == j ? 1.0 : 0.0);
-      e2 += ((i >> 6) == (j >> 6)) ? v * v : 2.0 * v * v;
-    }
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) e2 += __shfl_xor(e2, off);
-    if (lane == 0) red_e[wave] = e2;
-    __syncthreads();
-    double tot = 0.0;
-    for (int w = 0; w < CHOL_THREADS / 64; ++w) tot += red_e[w];
-    if (tot <= g.ns_tol * g.ns_tol) {       // also false for NaN
-      for (int e = t; e < kp * kp; e += CHOL_THREADS) {
-        const int i = e / kp, j = e - i * kp;
-        double v = 0.0;
-        if (i < k && j < k) {
-          const int a = ((i >> 6) >= (j >> 6)) ? i : j, b = ((i >> 6) >= (j >> 6)) ? j : i;
-          v = -0.5 * ((LDS_MODE ? Am[a * lda + b] : G[(int64_t)a * kp + b]) - (i == j ? 1.0 : 0.0));
-        }
-        g.ns_T[e] = (bf16_t)(float)v;
-      }
-      if (t == 0) *g.ns_flag = 1;
-      return;
-    }
-    if (t == 0) *g.ns_flag = 0;
-  }
 
   double trace_sum = 0.0;
   if (wave == 0) {
@@ -570,7 +578,7 @@ __global__ __launch_bounds__(256) void ns_finalize_kernel(const float* Q1, const
 
 static int gram_rows_per_chunk(int64_t m, int nblocks) {
   // aim for ~384 workgroups, at least 32 rows per chunk, at most 128 chunks
-  int64_t chunks = std::max<int64_t>(1, 384 / std::max(1, nblocks));
+  int64_t chunks = std::max<int64_t>(1, GRAM_TARGET_WGS / std::max(1, nblocks));
   chunks = std::min<int64_t>(chunks, 128);
   int64_t rows = ceil_div64(m, chunks);
   rows = std::max<int64_t>(32, ceil_div64(rows, 16) * 16);
@@ -586,8 +594,10 @@ static size_t gram_partial_bytes(int64_t m, int kp) {
   return (size_t)ceil_div64(m, rows) * nblocks * 4096 * sizeof(double);
 }
 
-static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t m, int kp,
-                            double* part, double* G, double* G_copy = nullptr) {
+// ns_e2 needs 16 * gram_nblocks(kp) doubles.
+static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t m, int kp, int k,
+                            double* part, double* G, double* G_copy = nullptr,
+                            bf16_t* ns_T = nullptr, double* ns_e2 = nullptr) {
   GramArgs g;
   g.Y = Y; g.ldy = ldy; g.m = m; g.kp = kp;
   g.nb64 = (kp + 63) / 64;
@@ -597,7 +607,7 @@ static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t 
   const int chunks = (int)ceil_div64(m, g.rows_per_chunk);
   LORACT_LAUNCH("gram", s, gram_mfma_kernel, dim3(chunks, nblocks), dim3(256), 0, g);
   LORACT_LAUNCH("gram_reduce", s, gram_reduce_kernel, dim3(16, nblocks), dim3(256), 0,
-                (const double*)part, chunks, nblocks, kp, G, G_copy);
+                (const double*)part, chunks, nblocks, kp, k, G, G_copy, ns_T, ns_e2);
   return LORACT_OK;
 }
 
