@@ -661,11 +661,15 @@ __global__ __launch_bounds__(256) void lora_vtt_kernel(const bf16_t* V, const fl
   const int cg = (int)(item / n);
   if (cg >= groups) return;
   f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-  for (int q = 0; q < k; ++q) {
-    const float v = (float)V[(int64_t)q * n + j];
-    const f32x4 tq = *(const f32x4*)(lv_T + q * rp + 4 * cg);
-    acc += v * tq;
+  int q = 0;
+  for (; q + 8 <= k; q += 8) {            // 8 independent loads in flight
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = (float)V[(int64_t)(q + u) * n + j];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc += v[u] * *(const f32x4*)(lv_T + (q + u) * rp + 4 * cg);
   }
+  for (; q < k; ++q) acc += (float)V[(int64_t)q * n + j] * *(const f32x4*)(lv_T + q * rp + 4 * cg);
 #pragma unroll
   for (int u = 0; u < 4; ++u)
     if (4 * cg + u < r) dA[j * r + 4 * cg + u] = scale * acc[u];
