@@ -628,7 +628,7 @@ static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) 
 static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
   g.row_tiles = (int)ceil_div64(g.m, 128);
   const int64_t colb = ceil_div64(g.n, RC_BN);
-  int64_t groups = std::max<int64_t>(1, 768 / colb);
+  int64_t groups = std::max<int64_t>(1, 512 / colb);   // two resident workgroups per CU
   groups = std::min<int64_t>(groups, g.row_tiles);
   dim3 grid((unsigned)colb, (unsigned)groups);
   switch ((g.k + 15) / 16) {
