@@ -149,6 +149,27 @@ int loract_gaussian_omega_t(void* omegaT_dev, int32_t l, int64_t n, int32_t dtyp
                             uint64_t seed, void* stream);
 
 /*
+ * Pre-norm unit, Section 3.3.  The activation that is stored (and handed to loract_compress) is
+ * the OUTPUT of the RMS normalisation, A = Norm(X) = X / RMS(X) * gamma (Eqs. 6-7), shared by
+ * Norm and the sub-layer; only the RMS vector (m floats) is kept beside the factors.
+ *
+ * forward:  rms_i = sqrt(mean_j X_ij^2 + eps), A_ij = X_ij / rms_i * gamma_j.
+ *   X_dev m x n (ld ldx), A_dev m x n out (ld lda), both of dtype; gamma_dev n floats;
+ *   rms_dev m floats out.
+ * backward (Eqs. 8-10): from the reconstructed A (= U V), the stored RMS vector and dA = dL/dA:
+ *   Xbar = A / gamma, dXbar = dA * gamma,
+ *   dX_ij = (dXbar_ij - Xbar_ij * mean_j(dXbar_ij Xbar_ij)) / rms_i.
+ *   A_dev, dA_dev, dX_dev m x n of dtype (leading dimensions lda, ldda, lddx); gamma must be
+ *   nonzero.  No workspace; enqueued on `stream`.
+ */
+int loract_prenorm_forward(const void* X_dev, int64_t m, int64_t n, int64_t ldx, int32_t dtype,
+                           const float* gamma_dev, float eps, void* A_dev, int64_t lda,
+                           float* rms_dev, void* stream);
+int loract_prenorm_backward(const void* A_dev, int64_t m, int64_t n, int64_t lda, int32_t dtype,
+                            const float* rms_dev, const float* gamma_dev, const void* dA_dev,
+                            int64_t ldda, void* dX_dev, int64_t lddx, void* stream);
+
+/*
  * Per-kernel timing with HIP events on the stream the kernels are launched on.
  * begin: start bracketing every kernel launch of this library with event records.
  * end:   stop, wait for the recorded events, and aggregate by kernel name.

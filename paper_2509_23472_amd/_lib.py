@@ -40,6 +40,10 @@ SIGNATURES = {
                                         ctypes.c_float, _vp, _vp, _sz, _vp]),
     "loract_rsvd": (ctypes.c_int, [_vp, _P(LoractParams), _vp, _vp, _vp, _vp, _sz, _vp, _vp]),
     "loract_gaussian_omega_t": (ctypes.c_int, [_vp, _i32, _i64, _i32, _u64, _vp]),
+    "loract_prenorm_forward": (ctypes.c_int, [_vp, _i64, _i64, _i64, _i32, _vp, ctypes.c_float, _vp, _i64,
+                                              _vp, _vp]),
+    "loract_prenorm_backward": (ctypes.c_int, [_vp, _i64, _i64, _i64, _i32, _vp, _vp, _vp, _i64, _vp,
+                                               _i64, _vp]),
     "loract_profile_begin": (ctypes.c_int, []),
     "loract_profile_end": (ctypes.c_int, []),
     "loract_profile_count": (ctypes.c_int, []),

@@ -217,6 +217,41 @@ def loract_rsvd(x: torch.Tensor, k: int, oversample: int = 0, power_iters: int =
     return u, v
 
 
+def loract_prenorm_forward(x: torch.Tensor, gamma: torch.Tensor, eps: float = 0.0
+                           ) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Section 3.3, Eqs. (6)-(7): A = X / RMS(X) * gamma and the RMS vector (float32, m)."""
+    _require_cuda(x, gamma)
+    if x.dim() != 2 or x.stride(1) != 1 or gamma.dtype != torch.float32 or gamma.numel() != x.shape[1] \
+            or not gamma.is_contiguous():
+        raise ValueError("need a 2-D X with unit column stride and a contiguous float32 gamma of length n")
+    m, n = x.shape
+    a = torch.empty((m, n), dtype=x.dtype, device=x.device)
+    rms = torch.empty((m,), dtype=torch.float32, device=x.device)
+    _check(_lib.load().loract_prenorm_forward(x.data_ptr(), m, n, x.stride(0) if m > 1 else n,
+                                              _dtype_code(x.dtype), gamma.data_ptr(), float(eps),
+                                              a.data_ptr(), n, rms.data_ptr(), _stream_ptr()),
+           "loract_prenorm_forward")
+    return a, rms
+
+
+def loract_prenorm_backward(a: torch.Tensor, rms: torch.Tensor, gamma: torch.Tensor,
+                            grad_a: torch.Tensor) -> torch.Tensor:
+    """Section 3.3, Eqs. (8)-(10): dL/dX from the (reconstructed) A, the RMS vector and dL/dA."""
+    _require_cuda(a, rms, gamma, grad_a)
+    if a.shape != grad_a.shape or a.dtype != grad_a.dtype or a.stride(1) != 1 or grad_a.stride(1) != 1:
+        raise ValueError("A and dA must have the same shape and dtype, unit column stride")
+    m, n = a.shape
+    if rms.dtype != torch.float32 or rms.numel() != m or gamma.dtype != torch.float32 or gamma.numel() != n:
+        raise ValueError("rms (m) and gamma (n) must be float32")
+    dx = torch.empty((m, n), dtype=a.dtype, device=a.device)
+    _check(_lib.load().loract_prenorm_backward(a.data_ptr(), m, n, a.stride(0) if m > 1 else n,
+                                               _dtype_code(a.dtype), rms.data_ptr(), gamma.data_ptr(),
+                                               grad_a.data_ptr(), grad_a.stride(0) if m > 1 else n,
+                                               dx.data_ptr(), n, _stream_ptr()),
+           "loract_prenorm_backward")
+    return dx
+
+
 def loract_profile_begin() -> None:
     _check(_lib.load().loract_profile_begin(), "loract_profile_begin")
 

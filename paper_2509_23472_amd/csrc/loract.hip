@@ -6,6 +6,7 @@
 #include "ortho_f64.h"
 #include "stream_bf16.h"
 #include "eig_jacobi.h"
+#include "prenorm.h"
 
 #include <algorithm>
 #include <cmath>
@@ -612,6 +613,44 @@ int loract_rsvd(const void* X_dev, const loract_params* p, const void* omegaT_de
                              U_dev, k, f_ek, 1, nullptr));
   return launch_gemm_f64("rsvd_wtb", s, Wk, k, 0, EK_F64, Bmat, n, 0, b_ek, nullptr, k, n, l, 1.0,
                          V_dev, n, f_ek, 1, nullptr);
+}
+
+static int prenorm_common(PrenormArgs* a, int64_t m, int64_t n, int32_t dtype) {
+  if (m < 1 || n < 1 || !dtype_ok(dtype)) return LORACT_ERR_INVALID_ARG;
+  if (a->ldx < n || a->ldo < n) return LORACT_ERR_INVALID_ARG;
+  a->m = m; a->n = n;
+  a->ek = dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
+  return LORACT_OK;
+}
+
+int loract_prenorm_forward(const void* X_dev, int64_t m, int64_t n, int64_t ldx, int32_t dtype,
+                           const float* gamma_dev, float eps, void* A_dev, int64_t lda,
+                           float* rms_dev, void* stream) {
+  if (!X_dev || !gamma_dev || !A_dev || !rms_dev) return LORACT_ERR_INVALID_ARG;
+  PrenormArgs a;
+  a.X = X_dev; a.ldx = ldx; a.dA = nullptr; a.ldda = 0; a.gamma = gamma_dev; a.rms = rms_dev;
+  a.out = A_dev; a.ldo = lda; a.eps = eps;
+  LORACT_TRY(prenorm_common(&a, m, n, dtype));
+  a.vec = dtype == LORACT_BF16 && n % 8 == 0 && sb_aligned(X_dev, ldx) && sb_aligned(A_dev, lda) &&
+          ((uintptr_t)gamma_dev) % 16 == 0;
+  LORACT_LAUNCH("prenorm_forward", (hipStream_t)stream, prenorm_forward_kernel,
+                dim3((unsigned)ceil_div64(m, 4)), dim3(256), 0, a);
+  return LORACT_OK;
+}
+
+int loract_prenorm_backward(const void* A_dev, int64_t m, int64_t n, int64_t lda, int32_t dtype,
+                            const float* rms_dev, const float* gamma_dev, const void* dA_dev,
+                            int64_t ldda, void* dX_dev, int64_t lddx, void* stream) {
+  if (!A_dev || !rms_dev || !gamma_dev || !dA_dev || !dX_dev || ldda < n) return LORACT_ERR_INVALID_ARG;
+  PrenormArgs a;
+  a.X = A_dev; a.ldx = lda; a.dA = dA_dev; a.ldda = ldda; a.gamma = gamma_dev; a.rms = (float*)rms_dev;
+  a.out = dX_dev; a.ldo = lddx; a.eps = 0.0f;
+  LORACT_TRY(prenorm_common(&a, m, n, dtype));
+  a.vec = dtype == LORACT_BF16 && n % 8 == 0 && sb_aligned(A_dev, lda) && sb_aligned(dA_dev, ldda) &&
+          sb_aligned(dX_dev, lddx) && ((uintptr_t)gamma_dev) % 16 == 0;
+  LORACT_LAUNCH("prenorm_backward", (hipStream_t)stream, prenorm_backward_kernel,
+                dim3((unsigned)ceil_div64(m, 4)), dim3(256), 0, a);
+  return LORACT_OK;
 }
 
 int loract_profile_begin(void) {
