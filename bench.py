@@ -321,6 +321,16 @@ def main() -> int:
         pipelined = {"streams": nstreams, "us_per_site": round(us_site, 1),
                      "gbps": round(x_bytes / us_site / 1e3, 1), "bit_identical_to_single_stream": bool(same)}
 
+    # pre-norm unit (Section 3.3) at the same shape: bandwidth-bound row kernels
+    gamma = torch.ones((n,), dtype=torch.float32, device="cuda")
+    a_n, rms_n = L.loract_prenorm_forward(x, gamma)
+    us_pf = timed(lambda: L.loract_prenorm_forward(x, gamma))
+    us_pb = timed(lambda: L.loract_prenorm_backward(xhat, rms_n, gamma, dy[:, :n] if n_out >= n else xhat))
+    prenorm = {"forward_us": round(us_pf, 1), "forward_gbps": round(2 * x_bytes / us_pf / 1e3, 1),
+               "backward_us": round(us_pb, 1), "backward_gbps": round(3 * x_bytes / us_pb / 1e3, 1),
+               "note": "algorithmic bytes: forward reads X writes A (2|X|), backward reads A, dA writes dX (3|X|)"}
+    del a_n
+
     if args.pmc_calibration:
         scratch = torch.empty_like(x)
         for _ in range(5):
@@ -380,6 +390,7 @@ def main() -> int:
         "roofline_streaming": roofline_streaming,
         "comparator": comparator,
         "pipelined": pipelined,
+        "prenorm": prenorm,
         "kernels": kernels,
     }
 
