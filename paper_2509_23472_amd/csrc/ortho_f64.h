@@ -84,27 +84,49 @@ __global__ __launch_bounds__(256) void gram_mfma_kernel(GramArgs g) {
 
   const bool a_ok0 = ca + lc < g.kp, a_ok1 = ca + 16 + lc < g.kp;
   const bool b_ok0 = cb + lc < g.kp, b_ok1 = cb + 16 + lc < g.kp;
-  // 16 rows per trip: all 16 loads are issued before the 16 matrix instructions consume them
-  for (int64_t r0 = r_begin; r0 < r_end; r0 += 16) {
-    float fa0[4], fa1[4], fb0[4], fb1[4];
+  const int ca_c0 = a_ok0 ? ca + lc : 0, ca_c1 = a_ok1 ? ca + 16 + lc : 0;
+  const int cb_c0 = b_ok0 ? cb + lc : 0, cb_c1 = b_ok1 ? cb + 16 + lc : 0;
+  // 16 rows per trip.  The 16 loads of a trip are unconditional, from clamped (in-bounds, hence
+  // finite) addresses, and zeroed by a multiplication: a select would put the load under a
+  // branch, where it is waited for on the spot.
+  const float ma0 = a_ok0 ? 1.0f : 0.0f, ma1 = a_ok1 ? 1.0f : 0.0f;
+  const float mb0 = b_ok0 ? 1.0f : 0.0f, mb1 = b_ok1 ? 1.0f : 0.0f;
+  // They are issued one trip ahead of the 16 matrix instructions that consume them.
+  float fa0[2][4], fa1[2][4], fb0[2][4], fb1[2][4];
+  auto load_trip = [&](int64_t r0, float* pa0, float* pa1, float* pb0, float* pb1) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       const int64_t row = r0 + 4 * u + lr;
       const bool rok = row < r_end;
       const float* yr = g.Y + (rok ? row : r_begin) * g.ldy;
-      fa0[u] = (rok && a_ok0) ? yr[ca + lc] : 0.0f;
-      fa1[u] = (rok && a_ok1) ? yr[ca + 16 + lc] : 0.0f;
-      fb0[u] = (rok && b_ok0) ? yr[cb + lc] : 0.0f;
-      fb1[u] = (rok && b_ok1) ? yr[cb + 16 + lc] : 0.0f;
+      pa0[u] = yr[ca_c0];
+      pa1[u] = yr[ca_c1];
+      pb0[u] = yr[cb_c0];
+      pb1[u] = yr[cb_c1];
     }
+  };
+  // the masks are applied here, at the point of use, so that nothing touches a loaded value
+  // (and waits for it) before the trip that consumes it
+  auto mac_trip = [&](int64_t r0, const float* pa0, const float* pa1, const float* pb0,
+                      const float* pb1) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
-      const double a0 = (double)fa0[u], a1 = (double)fa1[u];
-      const double b0 = (double)fb0[u], b1 = (double)fb1[u];
+      const float rm = (r0 + 4 * u + lr < r_end) ? 1.0f : 0.0f;
+      const double a0 = (double)(pa0[u] * (rm * ma0)), a1 = (double)(pa1[u] * (rm * ma1));
+      const double b0 = (double)(pb0[u] * (rm * mb0)), b1 = (double)(pb1[u] * (rm * mb1));
       acc[0][0] = mfma_f64(a0, b0, acc[0][0]);
       acc[0][1] = mfma_f64(a0, b1, acc[0][1]);
       acc[1][0] = mfma_f64(a1, b0, acc[1][0]);
       acc[1][1] = mfma_f64(a1, b1, acc[1][1]);
+    }
+  };
+  if (r_begin < r_end) load_trip(r_begin, fa0[0], fa1[0], fb0[0], fb1[0]);
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += 32) {
+    if (r0 + 16 < r_end) load_trip(r0 + 16, fa0[1], fa1[1], fb0[1], fb1[1]);
+    mac_trip(r0, fa0[0], fa1[0], fb0[0], fb1[0]);
+    if (r0 + 16 < r_end) {
+      if (r0 + 32 < r_end) load_trip(r0 + 32, fa0[0], fa1[0], fb0[0], fb1[0]);
+      mac_trip(r0 + 16, fa0[1], fa1[1], fb0[1], fb1[1]);
     }
   }
   double* out = g.part + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * 4096;
@@ -513,23 +535,44 @@ __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
   const bool rok = row < g.m;
   const float* yrow = g.Y + (rok ? row : 0) * g.ldy;
   f64x4 qb[NJ];
+  // Operands of block row J (the L blocks left of the diagonal, the inverted diagonal block and
+  // the Y values) are requested one block row ahead, so that their latency is covered by the
+  // matrix instructions of the row before.
+  double lop[2][4 * NJ], dop[2][4];
+  float yop[2][4];
+  auto fetch = [&](int J, double* lo, double* dd, float* yy) {
+    const double* lrow = g.L + (int64_t)(16 * J + lc) * g.kp;
+#pragma unroll
+    for (int I = 0; I < NJ; ++I) {
+      if (I < J) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) lo[4 * I + r] = lrow[16 * I + 4 * r + lr];
+      }
+    }
+    const double* drow = g.Dinv + ((int64_t)J * 16 + lc) * 16;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      dd[r] = drow[4 * r + lr];
+      yy[r] = yrow[16 * J + 4 * r + lr];  // rows past m read row 0 and are never stored
+    }
+  };
+  fetch(0, lop[0], dop[0], yop[0]);
 #pragma unroll
   for (int J = 0; J < NJ; ++J) {
+    const int cur = J & 1;
+    if (J + 1 < NJ) fetch(J + 1, lop[cur ^ 1], dop[cur ^ 1], yop[cur ^ 1]);
     f64x4 s = (f64x4){0.0, 0.0, 0.0, 0.0};
-    const double* lrow = g.L + (int64_t)(16 * J + lc) * g.kp;
 #pragma unroll
     for (int I = 0; I < J; ++I) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) s = mfma_f64(lrow[16 * I + 4 * r + lr], qb[I][r], s);
+      for (int r = 0; r < 4; ++r) s = mfma_f64(lop[cur][4 * I + r], qb[I][r], s);
     }
     f64x4 tt;
 #pragma unroll
-    for (int r = 0; r < 4; ++r)
-      tt[r] = (rok ? (double)yrow[16 * J + 4 * r + lr] : 0.0) - s[r];
+    for (int r = 0; r < 4; ++r) tt[r] = (double)yop[cur][r] - s[r];
     f64x4 o = (f64x4){0.0, 0.0, 0.0, 0.0};
-    const double* drow = g.Dinv + ((int64_t)J * 16 + lc) * 16;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) o = mfma_f64(drow[4 * r + lr], tt[r], o);
+    for (int r = 0; r < 4; ++r) o = mfma_f64(dop[cur][r], tt[r], o);
     qb[J] = o;
     if (rok) {
 #pragma unroll
