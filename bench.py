@@ -360,7 +360,7 @@ def main() -> int:
         torch.cuda.synchronize()
         rprof = L.loract_profile_end()
         us_trunc = sum(ms for nm, (ms, cnt) in rprof.items()
-                       if nm in ("jacobi_eig", "rsvd_bbt", "rsvd_qw", "rsvd_wtb")) * 1e3 / rsteps
+                       if nm in ("jacobi_eig", "truncate_bbt", "truncate_qw", "truncate_wtb")) * 1e3 / rsteps
         comparator = {"method": "rsvd (oversampling 8, 1 power iteration, rank %d)" % k,
                       "total_us": round(us_rsvd, 1), "truncation_us": round(us_trunc, 1),
                       "range_finder_us": round(us_rsvd - us_trunc, 1),

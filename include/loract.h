@@ -57,8 +57,10 @@ typedef struct {
   int64_t n;             /* columns of X (hidden size) */
   int64_t ldx;           /* leading dimension of X in elements, >= n */
   int32_t k;             /* target rank, 1 <= k <= min(m, n) */
-  int32_t l;             /* sketch columns.  loract_compress: 0 or k (Algorithm 1 samples k rows).
-                            loract_rsvd: k + oversampling, k <= l <= min(m, n, LORACT_MAX_RANK); 0 = k */
+  int32_t l;             /* sketch columns, k <= l <= min(m, n, LORACT_MAX_RANK); 0 = k.
+                            loract_compress: sampled rows (Algorithm 1 takes l = k; l > k is the
+                            sample of Theorem 4.3).  loract_rsvd: k + oversampling.  With l > k the
+                            l x n factor Q^T X is cut to its k leading singular triplets */
   int32_t t;             /* power iterations (Algorithm 1, steps 3-6); 0 on the hot path */
   int32_t x_dtype;       /* loract_dtype of X */
   int32_t factor_dtype;  /* loract_dtype of U and V; F32 input requires F32 factors */
@@ -89,8 +91,11 @@ int loract_workspace_bytes(const loract_params* p, size_t* bytes);
  * Forward pass, Section 3.1 Eqs. (2)-(3) by Algorithm 1 (Section 3.2):
  *   A_k = X[S, :] (k sampled rows), Y = X A_k^T, t x [Y = QR; Y = X (X^T Q)], Y = QR,
  *   U = Q (m x k, orthonormal columns), V = Q^T X (k x n).
+ * With l > k sampled rows (Theorem 4.3) Q has l columns and the factors are those of the k
+ * leading singular triplets of B = Q^T X: U = Q W_k, V = W_k^T B (W_k: k leading eigenvectors
+ * of B B^T), still m x k and k x n with orthonormal U.
  * X_dev        in,  m x n (ld = ldx), dtype x_dtype.
- * idx_host     in,  k ascending distinct row ids in host memory, or NULL to derive them from
+ * idx_host     in,  l ascending distinct row ids in host memory, or NULL to derive them from
  *              p->seed with loract_sample_indices.  Read before the call returns.
  * U_dev, V_dev out, m x k and k x n, contiguous, dtype factor_dtype.
  * ws_dev       scratch of at least loract_workspace_bytes(p) bytes; contents undefined after.

@@ -21,7 +21,8 @@ What it follows (all citations are to the LoRAct paper, arXiv 2509.23472):
 
 The method is an approximation (a randomized range finder), so there is no closed-form
 result to reach; the oracle takes the algorithm's steps literally in float64.  Library
-primitives used as steps: numpy matmul, and numpy's SVD in `rsvd` for the small l x n factor.
+primitives used as steps: numpy matmul, and numpy's SVD for the small l x n factor when l > k
+(`rsvd`, and `decompose` with more sampled rows than the rank).
 The thin QR is written out (Householder reflections) so that it can be pinned against LAPACK.
 
 Parity status: the paper prints no worked numerical example of the decomposition, so the
@@ -38,7 +39,9 @@ Readings of points the paper leaves open (each also listed in the design notes):
     Omega_1; duplicates would break it);
   - the sample is drawn by splitmix64 + Floyd's algorithm and sorted ascending;
   - t = 0 on the hot path; for t >= 1 only Y is orthonormalised, as Algorithm 1 writes it;
-  - QR sign convention diag(R) >= 0; a rank-deficient Y still yields an orthonormal Q.
+  - QR sign convention diag(R) >= 0; a rank-deficient Y still yields an orthonormal Q;
+  - more sampled rows than the rank (l > k, the setting of Theorem 4.3): Q spans the l-column
+    sketch and B = Q^T A is truncated to rank k by its SVD, as in `rsvd`.
 """
 from __future__ import annotations
 
@@ -130,26 +133,40 @@ def householder_qr(y: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
 
 
 def decompose(a: np.ndarray, k: int, t: int = 0, seed: int = 0,
-              idx: Optional[Sequence[int]] = None) -> Tuple[np.ndarray, np.ndarray]:
+              idx: Optional[Sequence[int]] = None, l: Optional[int] = None
+              ) -> Tuple[np.ndarray, np.ndarray]:
     """Algorithm 1: U (m x k, orthonormal columns), V (k x n) with A ~= U V.
 
-    `idx` overrides the seed-derived sample (k row ids); otherwise
-    idx = sample_indices(m, k, seed).
+    `idx` overrides the seed-derived sample (l row ids); otherwise
+    idx = sample_indices(m, l, seed).
+
+    `l` is the number of sampled rows.  Algorithm 1 takes l = k (the default).  Theorem 4.3
+    states its bound for a sample A_l of l rows with the test matrix Omega = A_l^T; the paper
+    does not say how rank-k factors are then returned, so for l > k this follows the reading
+    used for the randomized SVD it compares with: Q spans the l-column sketch, and the l x n
+    factor B = Q^T A is cut to its k leading singular triplets,
+    U = Q Ub[:, :k], V = diag(s[:k]) Vb^T[:k, :].
     """
     a = np.asarray(a, dtype=np.float64)
     m, n = a.shape
-    if not (1 <= k <= min(m, n)):
-        raise ValueError("need 1 <= k <= min(m, n)")
-    rows = sample_indices(m, k, seed) if idx is None else np.asarray(idx, dtype=np.int64)
-    if rows.shape != (k,):
-        raise ValueError("need exactly k sampled rows")
-    a_k = a[rows, :]                      # step 1: k sampled rows, k x n
-    y = a @ a_k.T                         # step 2: Y = A A_k^T, m x k
+    if l is None:
+        l = k
+    if not (1 <= k <= l <= min(m, n)):
+        raise ValueError("need 1 <= k <= l <= min(m, n)")
+    rows = sample_indices(m, l, seed) if idx is None else np.asarray(idx, dtype=np.int64)
+    if rows.shape != (l,):
+        raise ValueError("need exactly l sampled rows")
+    a_l = a[rows, :]                      # step 1: l sampled rows, l x n
+    y = a @ a_l.T                         # step 2: Y = A A_l^T, m x l
     for _ in range(t):                    # steps 3-6
         q, _ = householder_qr(y)
         y = a @ (a.T @ q)
     q, _ = householder_qr(y)              # step 7
-    return q, q.T @ a                     # step 8: U = Q, V = Q^T A
+    b = q.T @ a                           # step 8: U = Q, V = Q^T A
+    if l == k:
+        return q, b
+    ub, s, vbt = np.linalg.svd(b, full_matrices=False)
+    return q @ ub[:, :k], s[:k, None] * vbt[:k, :]
 
 
 def reconstruct(u: np.ndarray, v: np.ndarray) -> np.ndarray:

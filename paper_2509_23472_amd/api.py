@@ -100,12 +100,15 @@ def loract_compress(x: torch.Tensor, k: int, t: int = 0, seed: int = 0,
                     idx: Optional[Sequence[int]] = None,
                     factor_dtype: Optional[torch.dtype] = None,
                     out: Optional[Tuple[torch.Tensor, torch.Tensor]] = None,
-                    status: Optional[torch.Tensor] = None
+                    status: Optional[torch.Tensor] = None, l: int = 0
                     ) -> Tuple[torch.Tensor, torch.Tensor]:
-    """U (m x k), V (k x n) of Algorithm 1 for the GPU matrix `x`; enqueued on the current stream."""
+    """U (m x k), V (k x n) of Algorithm 1 for the GPU matrix `x`; enqueued on the current stream.
+
+    `l` > k samples l rows (Theorem 4.3) and cuts the result to rank k; 0 means l = k.
+    """
     _require_cuda(x)
     lib = _lib.load()
-    p = make_params(x, k, 0, t, seed, factor_dtype)
+    p = make_params(x, k, l, t, seed, factor_dtype)
     fdt = _torch_dtype(p.factor_dtype)
     if out is None:
         u = torch.empty((p.m, k), dtype=fdt, device=x.device)
@@ -118,9 +121,10 @@ def loract_compress(x: torch.Tensor, k: int, t: int = 0, seed: int = 0,
     ws = _workspace(loract_workspace_bytes(p), x.device)
     idx_arr = None
     if idx is not None:
-        if len(idx) != k:
-            raise ValueError("idx must hold k row ids")
-        idx_arr = (ctypes.c_int32 * k)(*[int(i) for i in idx])
+        n_idx = l if l else k
+        if len(idx) != n_idx:
+            raise ValueError("idx must hold l row ids (k when l is 0)")
+        idx_arr = (ctypes.c_int32 * n_idx)(*[int(i) for i in idx])
     if status is not None and (status.dtype != torch.int32 or not status.is_cuda):
         raise ValueError("status must be an int32 GPU tensor")
     _check(lib.loract_compress(x.data_ptr(), ctypes.byref(p), idx_arr, u.data_ptr(), v.data_ptr(),

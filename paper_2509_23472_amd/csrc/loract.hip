@@ -108,11 +108,9 @@ static int validate_params(const loract_params* p, bool rsvd, int* l_out) {
   if (!dtype_ok(p->x_dtype) || !dtype_ok(p->factor_dtype)) return LORACT_ERR_INVALID_ARG;
   if (p->k > p->m || p->k > p->n) return LORACT_ERR_INVALID_ARG;
   int l = p->l == 0 ? p->k : p->l;
-  if (rsvd) {
-    if (l < p->k || l > p->m || l > p->n) return LORACT_ERR_INVALID_ARG;
-  } else if (l != p->k) {
-    return LORACT_ERR_NOT_IMPLEMENTED;   // sampling more rows than the rank is not part of Algorithm 1
-  }
+  // l == k is Algorithm 1 (and the plain range finder); l > k (more sampled rows, or Gaussian
+  // oversampling) ends with a truncation of the l x n factor to rank k
+  if (l < p->k || l > p->m || l > p->n) return LORACT_ERR_INVALID_ARG;
   if (l > LORACT_MAX_RANK) return LORACT_ERR_UNSUPPORTED;
   if (p->x_dtype == LORACT_F32 && p->factor_dtype != LORACT_F32) return LORACT_ERR_UNSUPPORTED;
   *l_out = l;
@@ -147,7 +145,7 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
   pl->bgram_splits = 1;
-  if (rsvd && l > p->k) {
+  if (l > p->k) {
     pl->bgram_splits = pick_splits(lt * lt, n, 256);
     dpart = std::max(dpart, (size_t)pl->bgram_splits * l * l * 8);
   }
@@ -163,8 +161,8 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_fpart = take(fpart);
   const bool need_zt = p->t > 0 || rsvd;
   pl->off_zt = take(need_zt ? (size_t)l * n * (pl->bf16_path ? 2 : 8) : 0);
-  pl->off_bmat = take(rsvd && l > p->k ? (size_t)l * n * (pl->bf16_path ? 4 : 8) : 0);
-  pl->off_eig = take(rsvd && l > p->k ? (size_t)3 * l * l * 8 : 0);
+  pl->off_bmat = take(l > p->k ? (size_t)l * n * (pl->bf16_path ? 4 : 8) : 0);
+  pl->off_eig = take(l > p->k ? (size_t)3 * l * l * 8 : 0);
   pl->off_omega = take(rsvd ? (size_t)l * n * (pl->bf16_path ? 2 : 4) : 0);
   pl->total = off;
   return LORACT_OK;
@@ -401,32 +399,71 @@ int loract_workspace_bytes(const loract_params* p, size_t* bytes) {
   return LORACT_OK;
 }
 
+// l > k: B = Q^T X (l x n) with Q an orthonormal basis of the l-column sketch Y, then the rank-k
+// factors of the k leading singular triplets of B: U = Q W_k, V = W_k^T B, where the columns of
+// W_k are the k leading eigenvectors of B B^T (Section 3.2; the setting of Theorem 4.3 when the
+// sketch comes from l sampled rows).
+static int truncate_factors(const Ctx& c, void* Y, void* tmp, void* U_dev, void* V_dev) {
+  const loract_params* p = c.p;
+  hipStream_t s = c.s;
+  const int64_t m = p->m, n = p->n;
+  const int k = p->k, l = c.pl.l;
+  const int f_ek = p->factor_dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
+  void* Bmat = c.ws + c.pl.off_bmat;
+  const void* Q;
+  int q_ek, b_ek;
+  if (c.pl.bf16_path) {
+    // Q in fp32 (into the sketch buffer, free by the second round) for U = Q W_k, and its bf16
+    // copy for the projection on the matrix cores
+    bf16_t* Qb = ws_ptr<bf16_t>(c, c.pl.off_ub);
+    LORACT_TRY(orthonormalise_mfma(c, (const float*)Y, (float*)tmp, Y, EK_F32, Qb));
+    LORACT_TRY(project(c, Qb, EK_BF16, Bmat, EK_F32));
+    Q = Y; q_ek = EK_F32; b_ek = EK_F32;
+  } else {
+    LORACT_TRY(orthonormalise(c, Y, tmp, Y, EK_F64));
+    LORACT_TRY(project(c, Y, EK_F64, Bmat, EK_F64));
+    Q = Y; q_ek = EK_F64; b_ek = EK_F64;
+  }
+  double* eigA = ws_ptr<double>(c, c.pl.off_eig);
+  double* eigW = eigA + (size_t)l * l;
+  double* Wk = eigW + (size_t)l * l;
+  LORACT_TRY(launch_gemm_f64("truncate_bbt", s, Bmat, n, 1, b_ek, Bmat, n, 1, b_ek, nullptr, l, l, n, 1.0,
+                             eigA, l, EK_F64, c.pl.bgram_splits, ws_ptr<double>(c, c.pl.off_dpart)));
+  LORACT_TRY(launch_jacobi_eig(s, eigA, eigW, Wk, l, k));
+  // U = Q W_k (m x k),  V = W_k^T B (k x n)
+  LORACT_TRY(launch_gemm_f64("truncate_qw", s, Q, l, 1, q_ek, Wk, k, 0, EK_F64, nullptr, m, k, l, 1.0,
+                             U_dev, k, f_ek, 1, nullptr));
+  return launch_gemm_f64("truncate_wtb", s, Wk, k, 0, EK_F64, Bmat, n, 0, b_ek, nullptr, k, n, l, 1.0,
+                         V_dev, n, f_ek, 1, nullptr);
+}
+
 int loract_compress(const void* X_dev, const loract_params* p, const int32_t* idx_host,
                     void* U_dev, void* V_dev, void* ws_dev, size_t ws_bytes, void* stream,
                     int32_t* status_dev) {
   Ctx c;
   hipStream_t s = (hipStream_t)stream;
   LORACT_TRY(check_common(X_dev, p, U_dev, V_dev, ws_dev, ws_bytes, false, &c, s, status_dev));
-  const int k = p->k;
+  const int k = p->k, l = c.pl.l;
   IdxPack pack;
   memset(&pack, 0, sizeof(pack));
   if (idx_host) {
-    for (int i = 0; i < k; ++i) {
+    for (int i = 0; i < l; ++i) {
       if (idx_host[i] < 0 || idx_host[i] >= p->m) return LORACT_ERR_INVALID_ARG;
       if (i > 0 && idx_host[i] <= idx_host[i - 1]) return LORACT_ERR_INVALID_ARG;
       pack.v[i] = idx_host[i];
     }
   } else {
-    LORACT_TRY(sample_indices_host(p->m, k, p->seed, pack.v));
+    LORACT_TRY(sample_indices_host(p->m, l, p->seed, pack.v));
   }
   int32_t* idx_dev = ws_ptr<int32_t>(c, c.pl.off_idx);
-  LORACT_LAUNCH("store_indices", s, store_indices_kernel, dim3((k + 255) / 256), dim3(256), 0, pack,
-                k, idx_dev, status_dev);
+  LORACT_LAUNCH("store_indices", s, store_indices_kernel, dim3((l + 255) / 256), dim3(256), 0, pack,
+                l, idx_dev, status_dev);
   void* Y = c.ws + c.pl.off_a;
   void* tmp = c.ws + c.pl.off_b;
   LORACT_TRY(sketch(c, X_dev, p->ldx, idx_dev, Y));       // steps 1-2
   LORACT_TRY(power_iterations(c, Y, tmp));                // steps 3-6
-  return finish_factors(c, Y, tmp, U_dev, V_dev);         // steps 7-8
+  if (l == k) return finish_factors(c, Y, tmp, U_dev, V_dev);   // steps 7-8
+  return truncate_factors(c, Y, tmp, U_dev, V_dev);       // l > k sampled rows: rank-k truncation
 }
 
 int loract_reconstruct(const void* U_dev, const void* V_dev, int64_t m, int64_t n, int32_t k,
@@ -585,34 +622,7 @@ int loract_rsvd(const void* X_dev, const loract_params* p, const void* omegaT_de
   LORACT_TRY(power_iterations(c, Y, tmp));                             // t x [QR; Y = X (X^T Q)]
   if (l == k) return finish_factors(c, Y, tmp, U_dev, V_dev);          // no oversampling: U = Q, V = Q^T X
 
-  // oversampled: B = Q^T X (l x n), then truncate to the k leading singular triplets of B
-  const int f_ek = p->factor_dtype == LORACT_BF16 ? EK_BF16 : EK_F32;
-  void* Bmat = c.ws + c.pl.off_bmat;
-  const void* Q;
-  int q_ek, b_ek;
-  if (c.pl.bf16_path) {
-    // Q in fp32 (into the sketch buffer, free by the second round) for U = Q W_k, and its bf16
-    // copy for the projection on the matrix cores
-    bf16_t* Qb = ws_ptr<bf16_t>(c, c.pl.off_ub);
-    LORACT_TRY(orthonormalise_mfma(c, (const float*)Y, (float*)tmp, Y, EK_F32, Qb));
-    LORACT_TRY(project(c, Qb, EK_BF16, Bmat, EK_F32));
-    Q = Y; q_ek = EK_F32; b_ek = EK_F32;
-  } else {
-    LORACT_TRY(orthonormalise(c, Y, tmp, Y, EK_F64));
-    LORACT_TRY(project(c, Y, EK_F64, Bmat, EK_F64));
-    Q = Y; q_ek = EK_F64; b_ek = EK_F64;
-  }
-  double* eigA = ws_ptr<double>(c, c.pl.off_eig);
-  double* eigW = eigA + (size_t)l * l;
-  double* Wk = eigW + (size_t)l * l;
-  LORACT_TRY(launch_gemm_f64("rsvd_bbt", s, Bmat, n, 1, b_ek, Bmat, n, 1, b_ek, nullptr, l, l, n, 1.0,
-                             eigA, l, EK_F64, c.pl.bgram_splits, ws_ptr<double>(c, c.pl.off_dpart)));
-  LORACT_TRY(launch_jacobi_eig(s, eigA, eigW, Wk, l, k));
-  // U = Q W_k (m x k),  V = W_k^T B (k x n)
-  LORACT_TRY(launch_gemm_f64("rsvd_qw", s, Q, l, 1, q_ek, Wk, k, 0, EK_F64, nullptr, m, k, l, 1.0,
-                             U_dev, k, f_ek, 1, nullptr));
-  return launch_gemm_f64("rsvd_wtb", s, Wk, k, 0, EK_F64, Bmat, n, 0, b_ek, nullptr, k, n, l, 1.0,
-                         V_dev, n, f_ek, 1, nullptr);
+  return truncate_factors(c, Y, tmp, U_dev, V_dev);                   // oversampled: cut to rank k
 }
 
 static int prenorm_common(PrenormArgs* a, int64_t m, int64_t n, int32_t dtype) {

@@ -536,10 +536,11 @@ __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
   const float* yrow = g.Y + (rok ? row : 0) * g.ldy;
   f64x4 qb[NJ];
   // Operands of block row J (the L blocks left of the diagonal, the inverted diagonal block and
-  // the Y values) are requested one block row ahead, so that their latency is covered by the
-  // matrix instructions of the row before.
-  double lop[2][4 * NJ], dop[2][4];
-  float yop[2][4];
+  // the Y values) are requested TRSM_AHEAD block rows ahead, so that their latency is covered by
+  // the matrix instructions of the rows before (the first rows are short, hence more than one).
+  constexpr int TRSM_AHEAD = NJ <= 12 ? 2 : 1;
+  double lop[NJ][4 * NJ], dop[NJ][4];
+  float yop[NJ][4];
   auto fetch = [&](int J, double* lo, double* dd, float* yy) {
     const double* lrow = g.L + (int64_t)(16 * J + lc) * g.kp;
 #pragma unroll
@@ -556,11 +557,13 @@ __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
       yy[r] = yrow[16 * J + 4 * r + lr];  // rows past m read row 0 and are never stored
     }
   };
-  fetch(0, lop[0], dop[0], yop[0]);
+#pragma unroll
+  for (int J = 0; J < TRSM_AHEAD && J < NJ; ++J) fetch(J, lop[J], dop[J], yop[J]);
 #pragma unroll
   for (int J = 0; J < NJ; ++J) {
-    const int cur = J & 1;
-    if (J + 1 < NJ) fetch(J + 1, lop[cur ^ 1], dop[cur ^ 1], yop[cur ^ 1]);
+    const int cur = J;
+    if (J + TRSM_AHEAD < NJ)
+      fetch(J + TRSM_AHEAD, lop[J + TRSM_AHEAD], dop[J + TRSM_AHEAD], yop[J + TRSM_AHEAD]);
     f64x4 s = (f64x4){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int I = 0; I < J; ++I) {
@@ -599,12 +602,25 @@ __global__ __launch_bounds__(256) void ns_finalize_kernel(const float* Q1, const
   if (*flag == 0) return;
   const int c4 = kp >> 2;
   const int64_t total = m * c4;
+  const bool vec_ok = (l & 3) == 0 && ((uintptr_t)Q & 15) == 0 && ((uintptr_t)Qb & 7) == 0;
   for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
     const int64_t r = e / c4;
     const int c = (int)(e - r * c4) << 2;
     const f32x4 a = *(const f32x4*)(Q1 + r * kp + c);
     const f32x4 b = *(const f32x4*)(C + r * kp + c);
     const f32x4 q = a + b;
+    if (vec_ok) {
+      // the row pitch l and the base addresses keep groups of four aligned: vector stores
+      if (c < l) {
+        bf16x4 qh;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) qh[u] = (bf16_t)q[u];
+        if (q_ek == EK_F32) *(f32x4*)((float*)Q + r * l + c) = q;
+        else *(bf16x4*)((bf16_t*)Q + r * l + c) = qh;
+        if (Qb) *(bf16x4*)(Qb + r * l + c) = qh;
+      }
+      continue;
+    }
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
       if (c + u < l) {

@@ -40,8 +40,33 @@ __global__ __launch_bounds__(256) void sum_partials_kernel(const float* part, in
   for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
     const int64_t r = e / c4, c = (e - r * c4) << 2;
     const float* src = part + r * ld_part + c;
+    // loads are issued in batches so that their latencies overlap; the additions keep the
+    // ascending order of the splits
     f32x4 s4 = *(const f32x4*)src;
-    for (int z = 1; z < splits; ++z) s4 += *(const f32x4*)(src + (int64_t)z * split_stride);
+    int z = 1;
+    for (; z + 8 <= splits; z += 8) {
+      f32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = *(const f32x4*)(src + (int64_t)(z + u) * split_stride);
+#pragma unroll
+      for (int u = 0; u < 8; ++u) s4 += v[u];
+    }
+    if (z + 4 <= splits) {
+      f32x4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *(const f32x4*)(src + (int64_t)(z + u) * split_stride);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) s4 += v[u];
+      z += 4;
+    }
+    if (z + 2 <= splits) {
+      const f32x4 v0 = *(const f32x4*)(src + (int64_t)z * split_stride);
+      const f32x4 v1 = *(const f32x4*)(src + (int64_t)(z + 1) * split_stride);
+      s4 += v0;
+      s4 += v1;
+      z += 2;
+    }
+    if (z < splits) s4 += *(const f32x4*)(src + (int64_t)z * split_stride);
     if (out_ek == EK_F32) {
       *(f32x4*)((float*)out + r * ld_out + c) = s4;
     } else if (out_ek == EK_BF16) {

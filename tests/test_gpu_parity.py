@@ -311,3 +311,39 @@ def test_rsvd_with_device_generated_test_matrix():
     omega_t = synth.round_to_bf16(orc.gaussian_omega_t(20, 192, 1234).astype(np.float32))
     uo, vo = orc.rsvd(w.x.astype(np.float64), 16, oversample=4, omega_t=omega_t.astype(np.float64))
     print(check_compress_parity(w, u, v, oracle_factors=(uo, vo)))
+
+
+@pytest.mark.parametrize("dtype,m,n,k,l,t", [("f32", 500, 130, 8, 13, 0), ("bf16", 2100, 512, 32, 48, 0),
+                                             ("bf16", 1031, 256, 16, 40, 1), ("bf16", 4096, 1024, 64, 96, 0)])
+def test_oversampled_row_sample_truncated_to_rank_k(dtype, m, n, k, l, t):
+    # Theorem 4.3's setting: l > k sampled rows, factors cut to the k leading singular triplets
+    L = _lib()
+    w = _spectrum_workload(m, n, k, seed=3 * m + l, dtype=dtype, decay=0.9)
+    x = to_device(w.x, dtype)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    u, v = L.loract_compress(x, k, t=t, seed=w.seed, l=l, status=status)
+    xhat = L.loract_reconstruct(u, v)
+    torch.cuda.synchronize()
+    uo, vo = orc.decompose(w.x.astype(np.float64), k, t=t, seed=w.seed, l=l)
+    res = check_compress_parity(w, u, v, xhat, oracle_factors=(uo, vo),
+                                tol=1e-4 if dtype == "f32" else None)
+    print(res, "status", int(status.item()))
+    assert int(status.item()) == 0
+    # the extra sampled rows must not hurt: same matrix, l = k
+    u0, v0 = L.loract_compress(x, k, t=t, seed=w.seed)
+    torch.cuda.synchronize()
+    e_k = orc.rel_fro(to_host(u0) @ to_host(v0), w.x.astype(np.float64))
+    print("quality l=k %.4e  l=%d %.4e" % (e_k, l, res["quality_gpu"]))
+
+
+def test_oversampled_explicit_indices():
+    L = _lib()
+    w = _spectrum_workload(700, 192, 12, seed=17, dtype="bf16", decay=0.85)
+    idx = sorted(np.random.default_rng(3).choice(700, size=20, replace=False).tolist())
+    x = to_device(w.x, "bf16")
+    u, v = L.loract_compress(x, 12, idx=idx, l=20)
+    torch.cuda.synchronize()
+    uo, vo = orc.decompose(w.x.astype(np.float64), 12, idx=idx, l=20)
+    print(check_compress_parity(w, u, v, oracle_factors=(uo, vo)))
+    with pytest.raises(Exception):
+        L.loract_compress(x, 12, idx=idx[:12], l=20)

@@ -309,6 +309,62 @@ def test_sampling_and_gaussian_sketches_are_comparable():
     assert 0.5 <= e_s / e_g <= 2.0
 
 
+# ----------------------------------------------------------------------------- more sampled rows than the rank
+
+
+@pytest.mark.parametrize("m,n,k,l", [(60, 28, 5, 9), (48, 40, 8, 16), (70, 30, 6, 7)])
+def test_oversampled_decompose_is_best_rank_k_of_the_projected_matrix(m, n, k, l):
+    # Theorem 4.3's setting (l >= k sampled rows, Omega = A_l^T).  With P the orthogonal projector
+    # onto range(A A_l^T), built here from a least-squares solve and not from the oracle's QR,
+    # the rank-k factors must multiply to the best rank-k approximation of P A (Eckart-Young,
+    # Section 3.2), and the error splits by Pythagoras into the range-finder error plus the
+    # discarded singular values of P A.
+    a = _tiny(m, n, seed=3 * m + l, decay=0.8)
+    for seed in range(4):
+        idx = orc.sample_indices(m, l, seed)
+        y = a @ a[idx, :].T
+        pa = y @ np.linalg.lstsq(y, a, rcond=None)[0]
+        ub, sb, vbt = np.linalg.svd(pa, full_matrices=False)
+        best = (ub[:, :k] * sb[:k]) @ vbt[:k, :]
+        u, v = orc.decompose(a, k, seed=seed, l=l)
+        assert u.shape == (m, k) and v.shape == (k, n)
+        assert orc.orthogonality_defect(u) <= 1e-11
+        assert orc.rel_fro(u @ v, best) <= 1e-9
+        lhs = np.linalg.norm(a - u @ v) ** 2
+        rhs = np.linalg.norm(a - pa) ** 2 + np.sum(sb[k:l] ** 2)
+        assert abs(lhs - rhs) <= 1e-9 * np.linalg.norm(a) ** 2
+
+
+def test_oversampled_decompose_bounds_and_special_cases():
+    rng = np.random.default_rng(41)
+    # rank <= k input is recovered exactly whatever l (proof of Theorem 4.2, first case)
+    a = rng.standard_normal((50, 4)) @ rng.standard_normal((4, 35))
+    u, v = orc.decompose(a, 4, seed=2, l=9)
+    assert orc.rel_fro(u @ v, a) <= 1e-11
+    # l = k is Algorithm 1 itself
+    a = _tiny(64, 24, seed=8, decay=0.75)
+    u0, v0 = orc.decompose(a, 6, seed=3)
+    u1, v1 = orc.decompose(a, 6, seed=3, l=6)
+    assert np.array_equal(u0, u1) and np.array_equal(v0, v1)
+    # deterministic bound of Theorem 4.2 with a k x l block Omega_1 (full row rank), plus at most
+    # sigma_{k+1} for the truncation; and the Eckart-Young floor
+    _, s, vt = np.linalg.svd(a, full_matrices=False)
+    k, l = 6, 11
+    v1t, v2t, s2 = vt[:k, :], vt[k:, :], s[k:]
+    for seed in range(10):
+        idx = orc.sample_indices(64, l, seed)
+        omega = a[idx, :].T
+        range_bound = np.sqrt(s2[0] ** 2 + np.linalg.norm((s2[:, None] * (v2t @ omega)) @ np.linalg.pinv(v1t @ omega), 2) ** 2)
+        u, v = orc.decompose(a, k, seed=seed, l=l)
+        err = np.linalg.norm(a - u @ v, 2)
+        assert s[k] * (1 - 1e-12) <= err <= (s[k] + range_bound) * (1 + 1e-9)
+        assert np.all(np.linalg.svd(v, compute_uv=False) <= s[:k] * (1 + 1e-12))
+    # more sampled rows help on average
+    e_k = np.mean([np.linalg.norm(a - np.matmul(*orc.decompose(a, k, seed=sd))) for sd in range(30)])
+    e_2k = np.mean([np.linalg.norm(a - np.matmul(*orc.decompose(a, k, seed=sd, l=2 * k))) for sd in range(30)])
+    assert e_2k < e_k
+
+
 # ----------------------------------------------------------------------------- planted mistakes are caught
 
 
@@ -352,3 +408,25 @@ def test_planted_mistakes_violate_the_pins():
     assert not _theorem_4_2_holds(no_final_qr)
     assert not _theorem_4_2_holds(sketch_without_transpose)
     assert not _theorem_4_2_holds(wrong_projection_sign)
+
+
+def test_planted_truncation_mistakes_violate_the_oversampled_pin():
+    # the check of test_oversampled_decompose_is_best_rank_k_of_the_projected_matrix, applied to
+    # two plausible wrong truncations of the l-column basis
+    m, n, k, l = 60, 28, 5, 9
+    a = _tiny(m, n, seed=3 * m + l, decay=0.8)
+    idx = orc.sample_indices(m, l, 0)
+    y = a @ a[idx, :].T
+    pa = y @ np.linalg.lstsq(y, a, rcond=None)[0]
+    ub, sb, vbt = np.linalg.svd(pa, full_matrices=False)
+    best = (ub[:, :k] * sb[:k]) @ vbt[:k, :]
+
+    q, _ = orc.householder_qr(y)
+    first_columns = q[:, :k] @ (q[:, :k].T @ a)            # keeps k columns of Q instead of k triplets of B
+    b = q.T @ a
+    ubb, sbb, vbbt = np.linalg.svd(b, full_matrices=False)
+    unscaled = (q @ ubb[:, :k]) @ vbbt[:k, :]              # forgets the singular values in V
+    good = np.matmul(*orc.decompose(a, k, seed=0, l=l))
+    assert orc.rel_fro(good, best) <= 1e-9
+    assert orc.rel_fro(first_columns, best) > 1e-3
+    assert orc.rel_fro(unscaled, best) > 1e-3
