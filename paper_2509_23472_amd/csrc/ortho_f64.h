@@ -547,7 +547,8 @@ __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
     for (int I = 0; I < NJ; ++I) {
       if (I < J) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) lo[4 * I + r] = lrow[16 * I + 4 * r + lr];
+        for (int r = 0; r < 4; ++r)
+          lo[4 * I + r] = OF_SKIPPED(8) ? 1e-3 * (lc + r) : lrow[16 * I + 4 * r + lr];
       }
     }
     const double* drow = g.Dinv + ((int64_t)J * 16 + lc) * 16;
@@ -577,7 +578,7 @@ __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) o = mfma_f64(dop[cur][r], tt[r], o);
     qb[J] = o;
-    if (rok) {
+    if (rok && !(OF_SKIPPED(4) && J + 1 < NJ)) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int col = 16 * J + 4 * r + lr;

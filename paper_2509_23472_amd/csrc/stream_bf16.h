@@ -526,15 +526,32 @@ static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = 
 }
 
 // ---------------------------------------------------------------------------------------------
-// reconstruct: Xhat (m x n, bf16) = U (m x k) V (k x n).  A workgroup owns 128 columns: it stages
-// its V tile once (pair interleaved), then walks over row tiles of 128 rows.  The product is
-// formed transposed (rows of the MFMA tile = columns of Xhat) so that the U fragments come
-// straight from global memory as 16-byte loads; the finished tile is turned back through LDS and
-// written as full 256-byte row segments.
+// reconstruct: Xhat (m x n, bf16) = U (m x k) V (k x n), a product with a short inner dimension
+// whose cost is the m x n write.
+//
+// Work items are (column block of 128, row tile of 64), column block major; every workgroup
+// takes an equal contiguous share of them, so the grid always matches the machine.  For its
+// column block a workgroup keeps the V operand stationary IN REGISTERS (staged once through
+// LDS, pair interleaved, then read out as matrix-core fragments), and streams the U row tiles
+// -- contiguous 64 x k blocks of memory -- through a double-buffered LDS ring with asynchronous
+// global -> LDS copies, one tile ahead.  The product is formed transposed (rows of the MFMA tile
+// = columns of Xhat) so that a U fragment is one 16-byte LDS read; the finished tile is turned
+// back through LDS and written as full 256-byte row segments.  Stores are not waited for: they
+// drain while the next tile is multiplied.
+//
+// U tile layout in LDS: [row][2 NKS chunks of 16 bytes], chunk c of row r stored at position
+// (c + r) mod 2 NKS, which spreads the fragment reads of consecutive rows over the banks.
 
 #define RC_BN 128
+#define RC_BM 64
 #define RC_LDV (RC_BN + 4)   // words per pair-row of the V tile
 #define RC_LDC (RC_BN + 8)   // bf16 elements per row of the output staging tile
+#define RC_CS_BYTES (RC_BM * RC_LDC * 2)
+#ifdef RC_ABLATE   // development harness only: bit 0 skips the U copies, bit 1 most stores, bit 2 the products
+#define RC_SKIPPED(bit) ((RC_ABLATE) & (bit))
+#else
+#define RC_SKIPPED(bit) false
+#endif
 
 struct ReconArgs {
   const bf16_t* U;       // m x k, ld = k
@@ -543,97 +560,174 @@ struct ReconArgs {
   int k;
   bf16_t* Xhat;
   int64_t ldxh;
-  int row_tiles;         // ceil(m / 128)
+  int row_tiles;         // ceil(m / 64)
+  int64_t items;         // column blocks * row_tiles
 };
+
+// Workgroup barrier that first waits for this wave's LDS traffic but leaves vector-memory
+// operations (asynchronous copies, stores) in flight.
+__device__ inline void sb_barrier_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int NKS>   // number of 16-deep K steps = ceil(k / 16)
 __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
+  constexpr int CPR = 2 * NKS;                  // 16-byte chunks per U row in LDS
+  constexpr int UBUF = RC_BM * CPR * 16;        // bytes per U buffer = CPR wave-wide copies
+  constexpr int NCOPY_MIN = CPR / 4;            // fewest copy instructions any wave issues per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
-  unsigned int* Vs = (unsigned int*)sb_smem;                       // [NKS * 8][RC_LDV]
-  bf16_t* Cs = (bf16_t*)(Vs + NKS * 8 * RC_LDV);                   // [128][RC_LDC]
+  bf16_t* Cs = (bf16_t*)sb_smem;                                   // [64][RC_LDC]
+  unsigned char* Ub = sb_smem + RC_CS_BYTES;                       // 2 x UBUF
+  unsigned int* Vs = (unsigned int*)sb_smem;                       // [NKS * 8][RC_LDV], prologue only
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t col0 = (int64_t)blockIdx.x * RC_BN;
+  const int cvalid = g.k >> 3;                  // valid chunks per row (k is a multiple of 8)
   const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
                         (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f};
 
-  // stage V[:, col0 .. col0+128) pair interleaved
-  for (int c = t; c < NKS * 8 * 16; c += 256) {
-    const int p = c >> 4, ch = c & 15;
-    const int64_t col = col0 + ch * 8;
-    const bool cok = col + 8 <= g.n;
-    const bf16_t* src = g.V + (int64_t)(2 * p) * g.n + col;
-    const bf16x8 lo = (cok && 2 * p < g.k) ? *(const bf16x8*)src : zero8;
-    const bf16x8 hi = (cok && 2 * p + 1 < g.k) ? *(const bf16x8*)(src + g.n) : zero8;
-    u32x4 w0, w1;
-    sb_interleave(lo, hi, &w0, &w1);
-    unsigned int* d = Vs + p * RC_LDV + ch * 8;
-    *(u32x4*)d = w0;
-    *(u32x4*)(d + 4) = w1;
-  }
-  __syncthreads();
+  // copy of U rows [rt * 64, +64) into buffer `buf`; rows past m repeat the last row (never stored)
+  auto issue_copy = [&](int rt, int buf) {
+    const int64_t r0 = (int64_t)rt * RC_BM;
+#pragma unroll
+    for (int i = 0; i < (CPR + 3) / 4; ++i) {
+      const int ins = wave + 4 * i;
+      if (ins < CPR) {
+        const int p = ins * 64 + lane;
+        const int row = p / CPR, pos = p % CPR;
+        int c = pos - row % CPR;
+        if (c < 0) c += CPR;
+        int64_t grow = r0 + row;
+        if (grow > g.m - 1) grow = g.m - 1;
+        if (c < cvalid && !RC_SKIPPED(1))
+          sb_async16(g.U + grow * g.k + c * 8, Ub + buf * UBUF + ins * 1024);
+      }
+    }
+  };
 
-  for (int rt = blockIdx.y; rt < g.row_tiles; rt += gridDim.y) {
-    const int64_t r0 = (int64_t)rt * 128;
-    // U fragments of this wave's 64 rows, all K steps
-    bf16x8 b[NKS][2];
+  const int64_t item_begin = g.items * blockIdx.x / gridDim.x;
+  const int64_t item_end = g.items * (blockIdx.x + 1) / gridDim.x;
+  int64_t item = item_begin;
+  while (item < item_end) {
+    // ---- segment: the items of one column block
+    const int64_t cb = item / g.row_tiles;
+    const int rt_first = (int)(item - cb * g.row_tiles);
+    const int64_t rt_stop = rt_first + (item_end - item);
+    const int rt_last = (int)(rt_stop < g.row_tiles ? rt_stop : g.row_tiles);   // exclusive
+    item += rt_last - rt_first;
+    const int64_t col0 = cb * RC_BN;
+
+    __syncthreads();   // a previous segment is done with LDS (and its stores have been issued)
+    for (int c = t; c < NKS * 8 * 16; c += 256) {
+      const int p = c >> 4, ch = c & 15;
+      const int64_t col = col0 + ch * 8;
+      const bool cok = col + 8 <= g.n;
+      const bf16_t* src = g.V + (int64_t)(2 * p) * g.n + col;
+      const bf16x8 lo = (cok && 2 * p < g.k) ? *(const bf16x8*)src : zero8;
+      const bf16x8 hi = (cok && 2 * p + 1 < g.k) ? *(const bf16x8*)(src + g.n) : zero8;
+      u32x4 w0, w1;
+      sb_interleave(lo, hi, &w0, &w1);
+      unsigned int* d = Vs + p * RC_LDV + ch * 8;
+      *(u32x4*)d = w0;
+      *(u32x4*)(d + 4) = w1;
+    }
+    __syncthreads();
+    // this wave's V fragments: 64 columns of Xhat, all K steps
+    bf16x8 a[NKS][2];
 #pragma unroll
     for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
-        const int64_t row = r0 + wn * 64 + 32 * j + (lane & 31);
-        const int kk = ks * 16 + 8 * (lane >> 5);
-        b[ks][j] = (row < g.m && kk + 8 <= g.k) ? *(const bf16x8*)(g.U + row * g.k + kk) : zero8;
-      }
-    f32x16 acc[2][2];
-#pragma unroll
-    for (int i = 0; i < 2; ++i)
-#pragma unroll
-      for (int j = 0; j < 2; ++j)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-#pragma unroll
-    for (int ks = 0; ks < NKS; ++ks) {
-      bf16x8 a[2];
-#pragma unroll
       for (int i = 0; i < 2; ++i)
-        a[i] = sb_pair_frag(Vs, RC_LDV, ks * 8 + 4 * (lane >> 5), wm * 64 + 32 * i + (lane & 31));
-#pragma unroll
-      for (int i = 0; i < 2; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[ks][j], acc[i][j], 0, 0, 0);
+        a[ks][i] = sb_pair_frag(Vs, RC_LDV, ks * 8 + 4 * (lane >> 5), wm * 64 + 32 * i + (lane & 31));
+    __syncthreads();   // the V staging area is free: it overlaps Cs and the U buffers
+    if ((g.k & 15) != 0 && t < 2 * RC_BM) {
+      // k = 16 NKS - 8: the last chunk of every row is padding that no copy writes
+      const int buf = t / RC_BM, row = t % RC_BM;
+      *(bf16x8*)(Ub + buf * UBUF + (row * CPR + (CPR - 1 + row) % CPR) * 16) = zero8;
     }
-    // accumulator register r of lane l: column 8*(r/4) + 4*(l/32) + r%4 of Xhat, row l%32
+
+    issue_copy(rt_first, 0);
+    for (int rt = rt_first; rt < rt_last; ++rt) {
+      const int it = rt - rt_first, cur = it & 1;
+      const bool has_next = rt + 1 < rt_last;
+      // next tile into the other buffer: its last readers (tile it-1) are past a barrier
+      if (has_next) issue_copy(rt + 1, cur ^ 1);
+      // Wait for this tile's copies.  Younger than them, and allowed to stay in flight: the 4
+      // stores of the previous tile (every tile but the last of the matrix is full, so each
+      // wave issued exactly 4) and the copies just issued (at least NCOPY_MIN per wave).
+      if (has_next) {
+        if (it > 0) SB_WAIT_VMCNT(4 + NCOPY_MIN); else SB_WAIT_VMCNT(NCOPY_MIN);
+      } else {
+        if (it > 0) SB_WAIT_VMCNT(4); else SB_WAIT_VMCNT(0);
+      }
+      sb_barrier_lds();   // copies of all waves landed; previous tile's reads of Cs are complete
+
+      const unsigned char* ub = Ub + cur * UBUF;
+      f32x16 acc[2];
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
+        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
+      const int urow = wn * 32 + (lane & 31);
+      // U fragments are read four K steps ahead of the matrix instructions that use them
+      constexpr int NG = (NKS + 3) / 4;
+      bf16x8 b[2][4];
+      auto read_group = [&](int gi, bf16x8* dst) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int ks = 4 * gi + u;
+          if (ks < NKS) {
+            const int c = 2 * ks + (lane >> 5);
+            dst[u] = *(const bf16x8*)(ub + (urow * CPR + (c + urow) % CPR) * 16);
+          }
+        }
+      };
+      read_group(0, b[0]);
+#pragma unroll
+      for (int gi = 0; gi < NG; ++gi) {
+        if (gi + 1 < NG) read_group(gi + 1, b[(gi + 1) & 1]);
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int ks = 4 * gi + u;
+          if (ks < NKS && !RC_SKIPPED(4)) {
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][0], b[gi & 1][u], acc[0], 0, 0, 0);
+            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][1], b[gi & 1][u], acc[1], 0, 0, 0);
+          }
+        }
+      }
+      // accumulator register r of lane l: column 8*(r/4) + 4*(l/32) + r%4 of Xhat, row l%32
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
           bf16x4 o;
 #pragma unroll
-          for (int u = 0; u < 4; ++u) o[u] = (bf16_t)acc[i][j][4 * q + u];
-          const int row = wn * 64 + 32 * j + (lane & 31);
+          for (int u = 0; u < 4; ++u) o[u] = (bf16_t)acc[i][4 * q + u];
           const int col = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
-          *(bf16x4*)(Cs + row * RC_LDC + col) = o;
+          *(bf16x4*)(Cs + urow * RC_LDC + col) = o;
         }
-    __syncthreads();
+      sb_barrier_lds();
+      const int64_t r0 = (int64_t)rt * RC_BM;
+      bf16x8 o[4];
 #pragma unroll
-    for (int q = 0; q < 8; ++q) {
-      const int e = t + 256 * q;
-      const int row = e >> 4, ch = e & 15;
-      const int64_t grow = r0 + row, col = col0 + ch * 8;
-      if (grow < g.m && col + 8 <= g.n)
-        *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = *(const bf16x8*)(Cs + row * RC_LDC + ch * 8);
+      for (int q = 0; q < 4; ++q) {
+        const int e = t + 256 * q;
+        o[q] = *(const bf16x8*)(Cs + (e >> 4) * RC_LDC + (e & 15) * 8);
+      }
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int e = t + 256 * q;
+        const int row = e >> 4, ch = e & 15;
+        const int64_t grow = r0 + row, col = col0 + ch * 8;
+        if (grow < g.m && col + 8 <= g.n && !(RC_SKIPPED(2) && it > 0))
+          *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = o[q];
+      }
     }
-    __syncthreads();
   }
 }
 
 static size_t reconstruct_lds_bytes(int nks) {
-  return (size_t)nks * 8 * RC_LDV * sizeof(unsigned int) + (size_t)128 * RC_LDC * sizeof(bf16_t);
+  const size_t run = (size_t)RC_CS_BYTES + (size_t)2 * RC_BM * 2 * nks * 16;
+  const size_t stage = (size_t)nks * 8 * RC_LDV * sizeof(unsigned int);
+  return std::max(run, stage);
 }
 
 template <int NKS>
@@ -650,13 +744,16 @@ static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) 
   return LORACT_OK;
 }
 
+// Requires k % 8 == 0 and 16-byte aligned U, V, Xhat rows (checked by the caller).
 static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
-  g.row_tiles = (int)ceil_div64(g.m, 128);
-  const int64_t colb = ceil_div64(g.n, RC_BN);
-  int64_t groups = std::max<int64_t>(1, 512 / colb);   // two resident workgroups per CU
-  groups = std::min<int64_t>(groups, g.row_tiles);
-  dim3 grid((unsigned)colb, (unsigned)groups);
-  switch ((g.k + 15) / 16) {
+  const int nks = (g.k + 15) / 16;
+  g.row_tiles = (int)ceil_div64(g.m, RC_BM);
+  g.items = ceil_div64(g.n, RC_BN) * g.row_tiles;
+  // as many workgroups as stay resident: LDS allows 160 KB per CU, registers about 2 per CU
+  const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)reconstruct_lds_bytes(nks)));
+  const int64_t wgs = std::min<int64_t>(g.items, 256 * per_cu);
+  dim3 grid((unsigned)wgs);
+  switch (nks) {
 #define RC_CASE(N) case N: return launch_reconstruct_nks<N>(s, g, grid);
     RC_CASE(1) RC_CASE(2) RC_CASE(3) RC_CASE(4) RC_CASE(5) RC_CASE(6) RC_CASE(7) RC_CASE(8)
     RC_CASE(9) RC_CASE(10) RC_CASE(11) RC_CASE(12) RC_CASE(13) RC_CASE(14) RC_CASE(15)
