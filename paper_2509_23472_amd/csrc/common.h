@@ -109,3 +109,29 @@ struct KernelScope {
     int rc_ = (EXPR);                 \
     if (rc_ != LORACT_OK) return rc_; \
   } while (0)
+// ---------------------------------------------------------------------------------------------
+// Asynchronous global -> LDS copies (global_load_lds_dwordx4): every lane of a wave fetches 16
+// bytes from its own global address and the wave's 64 pieces land contiguously (lane i at
+// base + 16 i) in LDS, without passing through registers.  Several slabs can therefore be in
+// flight from HBM per workgroup at no register cost; s_waitcnt vmcnt tracks their arrival.
+// Because the LDS placement is fixed by the lane number, bank conflicts are avoided by choosing
+// WHICH global chunk each lane fetches (an XOR swizzle on the chunk index), not by padding.
+
+__device__ inline void sb_async16(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
+}
+// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding).
+#define SB_WAIT_VMCNT(n) \
+  __builtin_amdgcn_s_waitcnt(((n) & 15) | ((((n) >> 4) & 3) << 14) | (7 << 4) | (15 << 8))
+
+// Workgroup barrier that orders LDS traffic for the compiler but does not drain the vector-memory
+// queue: __syncthreads() would wait for every outstanding asynchronous copy and with it for the
+// slabs that are meant to stay in flight.  Callers first wait (SB_WAIT_VMCNT) for the copies they
+// are about to read; LDS reads of the slab being recycled have completed by then because their
+// results were consumed by matrix instructions earlier in program order.
+__device__ inline void sb_barrier_keep_copies() { asm volatile("s_barrier" ::: "memory"); }
+// Workgroup barrier that first waits for this wave's LDS traffic but leaves vector-memory
+// operations (asynchronous copies, stores) in flight.
+__device__ inline void sb_barrier_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+

@@ -154,8 +154,8 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->sketch_splits = 1;
   if (pl->bf16_path) {
     pl->sketch_splits = sketch_splits_for(m, n, pl->kp);
-    pl->proj_splits = std::max(pl->proj_splits, project_splits_for(m, n, l));
-    fpart = std::max((size_t)pl->proj_splits * l * n * 4,
+    // the matrix-core projection's partial tiles, or the generic product's split partials
+    fpart = std::max(std::max(project_part_floats(m, n, l) * 4, (size_t)pl->proj_splits * l * n * 4),
                      pl->sketch_splits > 1 ? (size_t)pl->sketch_splits * m * pl->kp * 4 : (size_t)0);
   }
   pl->off_fpart = take(fpart);
@@ -293,7 +293,6 @@ static int project(const Ctx& c, const void* Q, int q_ek, void* Bt, int out_ek) 
       ProjectArgs a;
       a.Q = (const bf16_t*)Q; a.ldq = l; a.X = (const bf16_t*)c.X; a.ldx = c.p->ldx; a.m = m; a.n = n;
       a.l = l; a.V = Bt; a.out_ek = out_ek; a.part = ws_ptr<float>(c, c.pl.off_fpart);
-      a.splits = project_splits_for(m, n, l); a.rows_per_split = 0;
       return launch_project_mfma(c.s, a);
     }
     return launch_gemm_bf16("project_generic", c.s, (const bf16_t*)Q, l, 0, (const bf16_t*)c.X,
@@ -493,7 +492,7 @@ int loract_reconstruct(const void* U_dev, const void* V_dev, int64_t m, int64_t 
 struct LoraPlan {
   int t_splits;
   int rp;                 // r rounded up to 16
-  int g_splits, p_splits; // K splits of dY B^T, row splits of U^T G
+  int g_splits;           // K splits of dY B^T
   size_t off_g, off_t, off_dpart, off_gpart, off_gsplit, off_ppart, off_tsplit, total;
 };
 static int make_lora_plan(int64_t m, int64_t n, int32_t k, int64_t n_out, int32_t r, LoraPlan* lp) {
@@ -503,13 +502,12 @@ static int make_lora_plan(int64_t m, int64_t n, int32_t k, int64_t n_out, int32_
   lp->t_splits = pick_splits(ceil_div64(k, 64), m, 128);
   lp->rp = (r + 15) / 16 * 16;
   lp->g_splits = sketch_splits_for(m, n_out, lp->rp);
-  lp->p_splits = project_splits_for(m, 2 * lp->rp, k);
   lp->off_g = take((size_t)m * lp->rp * 4);
   lp->off_t = take((size_t)k * r * 4);
   lp->off_dpart = take((size_t)lp->t_splits * k * r * 8);
   lp->off_gpart = take((size_t)lp->g_splits * m * lp->rp * 4);
   lp->off_gsplit = take((size_t)m * 2 * lp->rp * 2);
-  lp->off_ppart = take((size_t)lp->p_splits * k * 2 * lp->rp * 4);
+  lp->off_ppart = take(project_part_floats(m, 2 * lp->rp, k) * 4);
   lp->off_tsplit = take((size_t)k * 2 * lp->rp * 4);
   lp->total = off;
   return LORACT_OK;
@@ -555,7 +553,6 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
     ProjectArgs pa;
     pa.Q = (const bf16_t*)U_dev; pa.ldq = k; pa.X = Gsplit; pa.ldx = 2 * rp; pa.m = m; pa.n = 2 * rp;
     pa.l = k; pa.V = ws + lp.off_tsplit; pa.out_ek = EK_F32; pa.part = (float*)(ws + lp.off_ppart);
-    pa.splits = lp.p_splits; pa.rows_per_split = 0;
     LORACT_TRY(launch_project_mfma(s, pa, "lora_utg"));
     // dA = scale * V^T (T_hi + T_lo)
     const int64_t items = n * (rp / 4);

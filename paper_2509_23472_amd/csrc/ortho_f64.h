@@ -526,59 +526,99 @@ struct TrsmArgs {
   const int32_t* skip_flag;   // optional: the launch does nothing when *skip_flag != 0
 };
 
-template <int NJ>
-__global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
+// Workgroup = WAVES waves = 16 WAVES rows of Y.  The operands every wave needs -- block row J of
+// L left of the diagonal and the inverted diagonal block, together "panel J", 16 x 16 (J + 1)
+// doubles -- are staged in LDS once per workgroup by asynchronous global -> LDS copies instead of
+// being fetched by every wave:
+//   panels 0 .. J0-1 (J0 = min(NJ, 8), 6 for the widest) are copied up front, side by side in one 16-row array;
+//   panel J + 1 >= J0 is copied into the other half of a double buffer while step J runs.
+// The LDS row pitches are 2 modulo 32 doubles (or 18), which spreads the 16 rows that one matrix
+// instruction operand touches over distinct banks.
+#define TRSM_J0(NJ) ((NJ) < 8 ? (NJ) : ((NJ) > 16 ? 6 : 8))
+#define TRSM_TILE_FLOATS (16 * 20)     // per-wave staging tile for the stores: 16 rows, pitch 20 floats
+template <int NJ, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void trsm_apply_kernel(TrsmArgs g) {
+  constexpr int J0 = TRSM_J0(NJ);
+  constexpr int PK = 8 * J0 * (J0 + 1) + 2;           // pitch of the side-by-side array, in doubles
+  constexpr int PR = 16 * NJ + 2;                     // pitch of a double-buffer half
+  extern __shared__ __attribute__((aligned(16))) double trsm_lds[];
+  double* const ring = trsm_lds + 16 * PK;
+  float* const tile = (float*)(ring + (NJ > J0 ? 32 * PR : 0)) + (threadIdx.x >> 6) * TRSM_TILE_FLOATS;
   if (g.skip_flag && *g.skip_flag != 0) return;
-  const int lane = threadIdx.x;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int lc = lane & 15, lr = lane >> 4;
-  const int64_t row = (int64_t)blockIdx.x * 16 + lc;
+  const int64_t row = (int64_t)blockIdx.x * (16 * WAVES) + wave * 16 + lc;
   const bool rok = row < g.m;
-  const float* yrow = g.Y + (rok ? row : 0) * g.ldy;
-  f64x4 qb[NJ];
-  // Operands of block row J (the L blocks left of the diagonal, the inverted diagonal block and
-  // the Y values) are requested TRSM_AHEAD block rows ahead, so that their latency is covered by
-  // the matrix instructions of the rows before (the first rows are short, hence more than one).
-  constexpr int TRSM_AHEAD = NJ <= 12 ? 2 : 1;
-  double lop[NJ][4 * NJ], dop[NJ][4];
-  float yop[NJ][4];
-  auto fetch = [&](int J, double* lo, double* dd, float* yy) {
-    const double* lrow = g.L + (int64_t)(16 * J + lc) * g.kp;
-#pragma unroll
-    for (int I = 0; I < NJ; ++I) {
-      if (I < J) {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-          lo[4 * I + r] = OF_SKIPPED(8) ? 1e-3 * (lc + r) : lrow[16 * I + 4 * r + lr];
+  // every row of the wave exists: its store instructions per step can be counted
+  const bool full_wave = (int64_t)blockIdx.x * (16 * WAVES) + wave * 16 + 15 < g.m;
+  const float* yrow = g.Y + (rok ? row : 0) * g.ldy;   // rows past m read row 0 and are never stored
+  // 4 consecutive output columns per lane can be stored as one vector
+  const bool vec_ok = (g.ldq & 3) == 0 && ((uintptr_t)g.Q & 15) == 0 &&
+                      (!g.Qb || ((g.ldqb & 3) == 0 && ((uintptr_t)g.Qb & 7) == 0));
+
+  // Copy of panel J to `dst` (pitch in doubles): one wave-wide instruction per (panel row, 64
+  // pieces of 16 bytes), dealt round-robin to the waves; lanes past the row end stay idle.
+  auto copy_panel = [&](int J, double* dst, int pitch) {
+    const int pieces = 8 * (J + 1);
+    const int nq = (pieces + 63) / 64;
+    for (int e = wave; e < 16 * nq; e += WAVES) {
+      const int r = e / nq, q = e - r * nq;
+      const int c = 2 * (64 * q + lane);
+      if (c < 16 * (J + 1)) {
+        const double* src = c < 16 * J ? g.L + (int64_t)(16 * J + r) * g.kp + c
+                                        : g.Dinv + ((int64_t)J * 16 + r) * 16 + (c - 16 * J);
+        sb_async16(src, (unsigned char*)(dst + r * pitch) + q * 1024);
       }
     }
-    const double* drow = g.Dinv + ((int64_t)J * 16 + lc) * 16;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      dd[r] = drow[4 * r + lr];
-      yy[r] = yrow[16 * J + 4 * r + lr];  // rows past m read row 0 and are never stored
-    }
   };
+
 #pragma unroll
-  for (int J = 0; J < TRSM_AHEAD && J < NJ; ++J) fetch(J, lop[J], dop[J], yop[J]);
+  for (int J = 0; J < J0; ++J) copy_panel(J, trsm_lds + 8 * J * (J + 1), PK);
+  SB_WAIT_VMCNT(0);
+  __syncthreads();
+
+  f64x4 qb[NJ];
+  float ycur[4], ynext[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) ycur[r] = yrow[4 * r + lr];
 #pragma unroll
   for (int J = 0; J < NJ; ++J) {
-    const int cur = J;
-    if (J + TRSM_AHEAD < NJ)
-      fetch(J + TRSM_AHEAD, lop[J + TRSM_AHEAD], dop[J + TRSM_AHEAD], yop[J + TRSM_AHEAD]);
+    const bool ring_next = J + 1 >= J0 && J + 1 < NJ;
+    if (ring_next) copy_panel(J + 1, ring + ((J + 1) & 1) * 16 * PR, PR);
+    if (J + 1 < NJ) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ynext[r] = yrow[16 * (J + 1) + 4 * r + lr];
+    }
+    const double* pan = J < J0 ? trsm_lds + lc * PK + 8 * J * (J + 1) : ring + (J & 1) * 16 * PR + lc * PR;
     f64x4 s = (f64x4){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
     for (int I = 0; I < J; ++I) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) s = mfma_f64(lop[cur][4 * I + r], qb[I][r], s);
+      for (int r = 0; r < 4; ++r) s = mfma_f64(pan[16 * I + 4 * r + lr], qb[I][r], s);
     }
     f64x4 tt;
 #pragma unroll
-    for (int r = 0; r < 4; ++r) tt[r] = (double)yop[cur][r] - s[r];
+    for (int r = 0; r < 4; ++r) tt[r] = (double)ycur[r] - s[r];
     f64x4 o = (f64x4){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-    for (int r = 0; r < 4; ++r) o = mfma_f64(dop[cur][r], tt[r], o);
+    for (int r = 0; r < 4; ++r) o = mfma_f64(pan[16 * J + 4 * r + lr], tt[r], o);
     qb[J] = o;
-    if (rok && !(OF_SKIPPED(4) && J + 1 < NJ)) {
+    if (vec_ok && 16 * J + 16 <= g.out_cols) {
+      // The 16 x 16 block is turned through a wave-private LDS tile (LDS operations of one wave
+      // execute in order) so that every lane stores 4 consecutive columns at once.
+#pragma unroll
+      for (int r = 0; r < 4; ++r) tile[lc * 20 + 4 * r + lr] = (float)o[r];
+      const f32x4 v = *(const f32x4*)(tile + lc * 20 + 4 * lr);
+      bf16x4 vh;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) vh[u] = (bf16_t)v[u];
+      if (rok) {
+        const int col = 16 * J + 4 * lr;
+        if (g.out_ek == EK_F32) *(f32x4*)((float*)g.Q + row * g.ldq + col) = v;
+        else *(bf16x4*)((bf16_t*)g.Q + row * g.ldq + col) = vh;
+        if (g.Qb) *(bf16x4*)(g.Qb + row * g.ldqb + col) = vh;
+      }
+    } else if (rok) {
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         const int col = 16 * J + 4 * r + lr;
@@ -589,7 +629,43 @@ __global__ __launch_bounds__(64) void trsm_apply_kernel(TrsmArgs g) {
         }
       }
     }
+    if (J + 1 < NJ) {
+#pragma unroll
+      for (int r = 0; r < 4; ++r) ycur[r] = ynext[r];
+    }
+    if (ring_next) {
+      // The copies of panel J + 1 are older than this step's stores (1 per wave on the vector
+      // path, 2 with the second output; every column of a step that is not the last lies inside
+      // out_cols), so they have landed once at most that many operations are pending.  The barrier also orders this step's
+      // reads of its buffer half before the copy that the next step issues into it.
+      if (!full_wave || !vec_ok) SB_WAIT_VMCNT(0);
+      else if (g.Qb) SB_WAIT_VMCNT(2);
+      else SB_WAIT_VMCNT(1);
+      sb_barrier_lds();
+    }
   }
+}
+template <int NJ, int WAVES>
+static int launch_trsm_nj_waves(hipStream_t s, const TrsmArgs& g) {
+  constexpr int J0 = TRSM_J0(NJ);
+  constexpr size_t lds = ((size_t)16 * (8 * J0 * (J0 + 1) + 2) + (NJ > J0 ? (size_t)32 * (16 * NJ + 2) : 0)) *
+                             sizeof(double) + (size_t)WAVES * TRSM_TILE_FLOATS * sizeof(float);
+  static bool attr_done = false;
+  if (lds > 64 * 1024 && !attr_done) {
+    hipError_t e = hipFuncSetAttribute((const void*)trsm_apply_kernel<NJ, WAVES>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(trsm LDS)");
+    attr_done = true;
+  }
+  LORACT_LAUNCH("trsm_apply", s, (trsm_apply_kernel<NJ, WAVES>),
+                dim3((unsigned)ceil_div64(g.m, 16 * WAVES)), dim3(64 * WAVES), lds, g);
+  return LORACT_OK;
+}
+// Few rows: 64 per workgroup so that more CUs take part; many rows: 128, which halves the panel
+// traffic per row.
+template <int NJ>
+static int launch_trsm_nj(hipStream_t s, const TrsmArgs& g) {
+  return g.m >= 32768 ? launch_trsm_nj_waves<NJ, 8>(s, g) : launch_trsm_nj_waves<NJ, 4>(s, g);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -700,13 +776,6 @@ static int launch_chol_blocked(hipStream_t s, CholArgs a) {
     const size_t lds = chol_lds_bytes(a.kp, false);
     LORACT_LAUNCH("chol", s, chol_blocked_kernel<false>, dim3(1), dim3(512), lds, a);
   }
-  return LORACT_OK;
-}
-
-template <int NJ>
-static int launch_trsm_nj(hipStream_t s, const TrsmArgs& g) {
-  LORACT_LAUNCH("trsm_apply", s, trsm_apply_kernel<NJ>, dim3((unsigned)ceil_div64(g.m, 16)), dim3(64),
-                0, g);
   return LORACT_OK;
 }
 

@@ -98,29 +98,6 @@ static int launch_sum_partials(hipStream_t s, const float* part, int splits, int
 }
 
 // ---------------------------------------------------------------------------------------------
-// Asynchronous global -> LDS copies (global_load_lds_dwordx4): every lane of a wave fetches 16
-// bytes from its own global address and the wave's 64 pieces land contiguously (lane i at
-// base + 16 i) in LDS, without passing through registers.  Several slabs can therefore be in
-// flight from HBM per workgroup at no register cost; s_waitcnt vmcnt tracks their arrival.
-// Because the LDS placement is fixed by the lane number, bank conflicts are avoided by choosing
-// WHICH global chunk each lane fetches (an XOR swizzle on the chunk index), not by padding.
-
-__device__ inline void sb_async16(const void* gsrc, void* lds_wave_base) {
-  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
-                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
-}
-// s_waitcnt with only the vector-memory counter constrained (gfx9 encoding).
-#define SB_WAIT_VMCNT(n) \
-  __builtin_amdgcn_s_waitcnt(((n) & 15) | ((((n) >> 4) & 3) << 14) | (7 << 4) | (15 << 8))
-
-// Workgroup barrier that orders LDS traffic for the compiler but does not drain the vector-memory
-// queue: __syncthreads() would wait for every outstanding asynchronous copy and with it for the
-// slabs that are meant to stay in flight.  Callers first wait (SB_WAIT_VMCNT) for the copies they
-// are about to read; LDS reads of the slab being recycled have completed by then because their
-// results were consumed by matrix instructions earlier in program order.
-__device__ inline void sb_barrier_keep_copies() { asm volatile("s_barrier" ::: "memory"); }
-
-// ---------------------------------------------------------------------------------------------
 // sketch: Y (m x kp, fp32) = X (m x n) * Bt^T, Bt = l rows of length n (optionally gathered).
 //
 // LDS slab layout, both operands: [row][64 K] as 8 chunks of 16 bytes per 128-byte row, chunk c of
@@ -345,11 +322,26 @@ __device__ inline bf16x8 sb_pair_frag(const unsigned int* tile, int ldw, int p0,
 }
 
 // ---------------------------------------------------------------------------------------------
-// project: V (l x n) = Q^T X with Q (m x l, bf16, ld = ldq) and X (m x n): long reduction over
-// the rows, split across workgroups; each workgroup owns a (BMQ x 128) tile of V for its rows.
+// project: V (l x n) = Q^T X with Q (m x l, bf16, ld = ldq) and X (m x n, bf16): a long reduction
+// over the rows in which BOTH operands are stored with the reduction index as the slow one.
+//
+// Slabs of 64 rows of X (BNX columns) and of Q (BMQ columns) are brought into LDS exactly as they
+// lie in memory, row major, by asynchronous global -> LDS copies, several slabs ahead.  The
+// matrix-core fragments (8 consecutive reduction indices of one column) are produced by the
+// transposing LDS read ds_read_b64_tr_b16: within a group of 16 lanes, lane s supplies the
+// address of 4 consecutive columns of row s / 4, and lane j receives the 4 rows of column j.
+// Chunk c (16 bytes) of slab row r is stored at chunk position c ^ 2 (r & 3), so that the four
+// rows a 16-lane group reads fall into different banks.
+//
+// Work items are (output tile of BMQ x BNX, slab), tile major; every workgroup takes an equal
+// contiguous share, writes one fp32 partial tile per output tile it touched, and
+// project_sum_kernel adds the partial tiles of each output tile in workgroup order.
 
-#define PJ_BN 128
-#define PJ_LDX (PJ_BN + 4)     // words per pair-row of the X slab
+#ifdef PJ_ABLATE   // development harness only: bit 0 skips the copies, bit 1 the products, bit 2 the LDS reads
+#define PJ_SKIPPED(bit) ((PJ_ABLATE) & (bit))
+#else
+#define PJ_SKIPPED(bit) false
+#endif
 
 struct ProjectArgs {
   const bf16_t* Q;
@@ -360,169 +352,296 @@ struct ProjectArgs {
   int l;                   // columns of Q = rows of V
   void* V;                 // l x n, ld = n
   int out_ek;              // EK_BF16 or EK_F32
-  float* part;             // [splits][l][n]
-  int splits;
-  int64_t rows_per_split;  // multiple of SB_BK
+  float* part;             // project_part_floats(m, n, l) floats
+  // filled in by the launcher
+  int slabs;               // ceil(m / 64)
+  int col_blocks;          // ceil(n / bnx)
+  int64_t items;           // output tiles * slabs
+  int wgs;                 // workgroups sharing the items
+  int segs_max;            // partial tiles reserved per workgroup
+  int bmq, bnx;            // rows and columns of an output tile
 };
 
-template <int NTQ>
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+
+__device__ inline s16x4 sb_read_tr(const unsigned char* lds_ptr) {
+  return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)lds_ptr);
+}
+
+// Output tile (64 NTQ) x (64 NTX), waves 2 x 2, each with NTQ x NTX matrix-core tiles.
+template <int NTQ, int NTX, int STAGES>
 __global__ __launch_bounds__(256) void project_mfma_kernel(ProjectArgs g) {
-  constexpr int BMQ = 64 * NTQ;
-  constexpr int LDQW = BMQ + 4;
+  constexpr int BMQ = 64 * NTQ, BNX = 64 * NTX;
+  constexpr int CQ = BMQ / 8, CX = BNX / 8;        // 16-byte chunks per slab row
+  constexpr int QPITCH = BMQ * 2, XPITCH = BNX * 2;
+  constexpr int X_BYTES = SB_BK * XPITCH, Q_BYTES = SB_BK * QPITCH;
+  constexpr int STAGE_BYTES = X_BYTES + Q_BYTES;
+  constexpr int LOADS = 2 * NTQ + 2 * NTX;         // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
-  unsigned int* Qs = (unsigned int*)sb_smem;            // [2][32][LDQW]
-  unsigned int* Xs = Qs + 2 * 32 * LDQW;                // [2][32][PJ_LDX]
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t col0 = (int64_t)blockIdx.x * PJ_BN;
-  const int q0 = blockIdx.y * BMQ;
-  const int64_t rbeg = (int64_t)blockIdx.z * g.rows_per_split;
-  const int64_t rend = (rbeg + g.rows_per_split < g.m) ? rbeg + g.rows_per_split : g.m;
-  const int nslab = (int)((rend - rbeg + SB_BK - 1) / SB_BK);
 
-  // X slab: 32 pair-rows x 16 chunks = 512 pair-chunks, 2 per thread.
-  // Q slab: 32 pair-rows x BMQ/8 chunks = 256 NTQ pair-chunks, NTQ per thread.
-  bf16x8 xlo[2], xhi[2], qlo[NTQ], qhi[NTQ];
-  const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
-                        (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f};
-  auto gload = [&](int64_t r0) {
+  // fragment addresses inside a stage (for K step 0, first half): lane s of a 16-lane group points
+  // at row s / 4, columns 4 (s % 4) .. + 3 of the group's 16 columns; lanes 32..63 take rows + 8
+  const int s16 = lane & 15, cg = (lane >> 4) & 1, kg = lane >> 5;
+  const int frow = 8 * kg + (s16 >> 2);
+  int x_off[NTX], q_off[NTQ];
 #pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = t + 256 * i;
-      const int p = c >> 4, ch = c & 15;
-      const int64_t r = r0 + 2 * p, col = col0 + ch * 8;
-      const bool cok = col + 8 <= g.n;
-      const bf16_t* src = g.X + r * g.ldx + col;
-      xlo[i] = (cok && r < rend) ? *(const bf16x8*)src : zero8;
-      xhi[i] = (cok && r + 1 < rend) ? *(const bf16x8*)(src + g.ldx) : zero8;
-    }
+  for (int j = 0; j < NTX; ++j) {
+    const int col = wn * 32 * NTX + 32 * j + 16 * cg + 4 * (s16 & 3);
+    x_off[j] = frow * XPITCH + (((col >> 3) ^ (2 * (s16 >> 2))) << 4) + (col & 7) * 2;
+  }
 #pragma unroll
-    for (int i = 0; i < NTQ; ++i) {
-      const int c = t + 256 * i;
-      const int p = c / (BMQ / 8), ch = c % (BMQ / 8);
-      const int64_t r = r0 + 2 * p;
-      const int qc = q0 + ch * 8;
-      const bool cok = qc + 8 <= g.l;
-      const bf16_t* src = g.Q + r * g.ldq + qc;
-      qlo[i] = (cok && r < rend) ? *(const bf16x8*)src : zero8;
-      qhi[i] = (cok && r + 1 < rend) ? *(const bf16x8*)(src + g.ldq) : zero8;
-    }
-  };
-  auto lstore = [&](int buf) {
-    unsigned int* Xb = Xs + buf * 32 * PJ_LDX;
-    unsigned int* Qb = Qs + buf * 32 * LDQW;
-#pragma unroll
-    for (int i = 0; i < 2; ++i) {
-      const int c = t + 256 * i;
-      u32x4 w0, w1;
-      sb_interleave(xlo[i], xhi[i], &w0, &w1);
-      unsigned int* d = Xb + (c >> 4) * PJ_LDX + (c & 15) * 8;
-      *(u32x4*)d = w0;
-      *(u32x4*)(d + 4) = w1;
-    }
-#pragma unroll
-    for (int i = 0; i < NTQ; ++i) {
-      const int c = t + 256 * i;
-      u32x4 w0, w1;
-      sb_interleave(qlo[i], qhi[i], &w0, &w1);
-      unsigned int* d = Qb + (c / (BMQ / 8)) * LDQW + (c % (BMQ / 8)) * 8;
-      *(u32x4*)d = w0;
-      *(u32x4*)(d + 4) = w1;
-    }
-  };
-
-  f32x16 acc[NTQ][2];
-#pragma unroll
-  for (int i = 0; i < NTQ; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
-  gload(rbeg);
-  lstore(0);
-  __syncthreads();
-  for (int s = 0; s < nslab; ++s) {
-    const int cur = s & 1;
-    if (s + 1 < nslab) gload(rbeg + (int64_t)(s + 1) * SB_BK);
-    const unsigned int* Xb = Xs + cur * 32 * PJ_LDX;
-    const unsigned int* Qb = Qs + cur * 32 * LDQW;
-#pragma unroll
-    for (int ks = 0; ks < SB_BK; ks += 16) {
-      const int p0 = (ks >> 1) + 4 * (lane >> 5);
-      bf16x8 a[NTQ], b[2];
-#pragma unroll
-      for (int i = 0; i < NTQ; ++i) a[i] = sb_pair_frag(Qb, LDQW, p0, wm * 32 * NTQ + 32 * i + (lane & 31));
-#pragma unroll
-      for (int j = 0; j < 2; ++j) b[j] = sb_pair_frag(Xb, PJ_LDX, p0, wn * 64 + 32 * j + (lane & 31));
-#pragma unroll
-      for (int i = 0; i < NTQ; ++i)
-#pragma unroll
-        for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
-    }
-    if (s + 1 < nslab) lstore(cur ^ 1);
-    __syncthreads();
+  for (int i = 0; i < NTQ; ++i) {
+    const int col = wm * 32 * NTQ + 32 * i + 16 * cg + 4 * (s16 & 3);
+    q_off[i] = X_BYTES + frow * QPITCH + (((col >> 3) ^ (2 * (s16 >> 2))) << 4) + (col & 7) * 2;
   }
 
-  // partial tile: rows = columns of Q, columns = columns of X
-  float* dst = g.part + (int64_t)blockIdx.z * g.l * g.n;
+  const int64_t item_begin = g.items * blockIdx.x / gridDim.x;
+  const int64_t item_end = g.items * (blockIdx.x + 1) / gridDim.x;
+  int64_t item = item_begin;
+  int seg = 0;
+  while (item < item_end) {
+    // ---- segment: consecutive slabs of one output tile
+    const int64_t tile = item / g.slabs;
+    const int s_beg = (int)(item - tile * g.slabs);
+    const int64_t s_stop = s_beg + (item_end - item);
+    const int s_end = (int)(s_stop < g.slabs ? s_stop : g.slabs);     // exclusive
+    const int nslab = s_end - s_beg;
+    item += nslab;
+    const int qb = (int)(tile / g.col_blocks), cb = (int)(tile - (int64_t)qb * g.col_blocks);
+    const int64_t col0 = (int64_t)cb * BNX;
+    const int q0 = qb * BMQ;
+
+    // copies of slab sl of the segment; rows past m repeat the last row and are zeroed when the
+    // fragments are read.  Addresses are rebuilt per copy from a few values to keep registers free.
+    const bf16_t* const x_col = g.X + col0;
+    const bf16_t* const q_col = g.Q + q0;
+    auto issue = [&](int sl) {          // sl: slab index within the segment
+      unsigned char* st = sb_smem + (sl % STAGES) * STAGE_BYTES;
+      const int64_t r0 = (int64_t)(s_beg + sl) * SB_BK;
 #pragma unroll
-  for (int i = 0; i < NTQ; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j) {
-      const int64_t col = col0 + wn * 64 + 32 * j + (lane & 31);
-      if (col >= g.n) continue;
-#pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int q = q0 + wm * 32 * NTQ + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (q < g.l) dst[(int64_t)q * g.n + col] = acc[i][j][r];
+      for (int i = 0; i < 2 * NTX; ++i) {
+        const int row = (wave * 2 * NTX + i) * (64 / CX) + lane / CX;
+        const int ch = (lane % CX) ^ (2 * (row & 3));
+        int64_t grow = r0 + row;
+        if (grow > g.m - 1) grow = g.m - 1;
+        if (col0 + ch * 8 + 8 <= g.n && !PJ_SKIPPED(1))
+          sb_async16(x_col + grow * g.ldx + ch * 8, st + (wave * 2 * NTX + i) * 1024);
       }
+#pragma unroll
+      for (int i = 0; i < 2 * NTQ; ++i) {
+        const int row = (wave * 2 * NTQ + i) * (64 / CQ) + lane / CQ;
+        const int ch = (lane % CQ) ^ (2 * (row & 3));
+        int64_t grow = r0 + row;
+        if (grow > g.m - 1) grow = g.m - 1;
+        if (q0 + ch * 8 + 8 <= g.l && !PJ_SKIPPED(1))
+          sb_async16(q_col + grow * g.ldq + ch * 8, st + X_BYTES + (wave * 2 * NTQ + i) * 1024);
+      }
+    };
+
+    f32x16 acc[NTQ][NTX];
+#pragma unroll
+    for (int i = 0; i < NTQ; ++i)
+#pragma unroll
+      for (int j = 0; j < NTX; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+    // fragments of K step ks of a stage
+    auto read_frags = [&](const unsigned char* st, int ks, s16x8* a, s16x8* b) {
+#pragma unroll
+      for (int i = 0; i < NTQ; ++i) {
+        const s16x4 lo = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + q_off[i] + (16 * ks) * QPITCH);
+        const s16x4 hi = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + q_off[i] + (16 * ks + 4) * QPITCH);
+        a[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+#pragma unroll
+      for (int j = 0; j < NTX; ++j) {
+        const s16x4 lo = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + x_off[j] + (16 * ks) * XPITCH);
+        const s16x4 hi = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + x_off[j] + (16 * ks + 4) * XPITCH);
+        b[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+      }
+    };
+    // one slab: 4 K steps of 16 rows, the fragments of a step read while the step before is multiplied
+    auto slab_mac = [&](const unsigned char* st) {
+      s16x8 a[2][NTQ], b[2][NTX];
+      read_frags(st, 0, a[0], b[0]);
+#pragma unroll
+      for (int ks = 0; ks < 4; ++ks) {
+        if (ks + 1 < 4) read_frags(st, ks + 1, a[(ks + 1) & 1], b[(ks + 1) & 1]);
+        if (!PJ_SKIPPED(2))
+#pragma unroll
+        for (int i = 0; i < NTQ; ++i)
+#pragma unroll
+          for (int j = 0; j < NTX; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[ks & 1][i]),
+                                                                __builtin_bit_cast(bf16x8, b[ks & 1][j]),
+                                                                acc[i][j], 0, 0, 0);
+      }
+    };
+
+#pragma unroll
+    for (int p = 0; p < STAGES - 1; ++p)
+      if (p < nslab) issue(p);
+#pragma nounroll
+    for (int sl = 0; sl < nslab; ++sl) {
+      // slab sl has landed once at most the copies of the (STAGES - 2) younger slabs are pending
+      if (sl + STAGES - 1 <= nslab) SB_WAIT_VMCNT((STAGES - 2) * LOADS);
+      else SB_WAIT_VMCNT(0);
+      sb_barrier_keep_copies();                      // everyone's copies landed; slab sl-1 is consumed
+      if (sl + STAGES - 1 < nslab) issue(sl + STAGES - 1);
+      unsigned char* st = sb_smem + (sl % STAGES) * STAGE_BYTES;
+      const int64_t left = g.m - (int64_t)(s_beg + sl) * SB_BK;
+      if (left < SB_BK) {
+        // last slab of the matrix: its rows past m (copies of row m - 1) are cleared in LDS
+        const u32x4 z = {0u, 0u, 0u, 0u};
+        for (int e = (int)left * (XPITCH / 16) + t; e < SB_BK * (XPITCH / 16); e += 256)
+          *(u32x4*)(st + e * 16) = z;
+        for (int e = (int)left * (QPITCH / 16) + t; e < SB_BK * (QPITCH / 16); e += 256)
+          *(u32x4*)(st + X_BYTES + e * 16) = z;
+        sb_barrier_lds();
+      }
+      slab_mac(st);
     }
+    sb_barrier_keep_copies();                        // the stages may be refilled by a next segment
+
+    // partial tile: rows = columns of Q, columns = columns of X
+    float* dst = g.part + ((int64_t)blockIdx.x * g.segs_max + seg) * (BMQ * BNX);
+#pragma unroll
+    for (int i = 0; i < NTQ; ++i)
+#pragma unroll
+      for (int j = 0; j < NTX; ++j) {
+        const int colw = wn * 32 * NTX + 32 * j + (lane & 31);
+        if (col0 + colw >= g.n) continue;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int qw = wm * 32 * NTQ + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          if (q0 + qw < g.l && !(PJ_SKIPPED(8) && acc[i][j][r] == 0.0f)) dst[qw * BNX + colw] = acc[i][j][r];
+        }
+      }
+    ++seg;
+  }
 }
 
-static inline int project_ntq_for(int l) { return l <= 64 ? 1 : (l <= 128 ? 2 : 4); }
-static size_t project_lds_bytes(int ntq) {
-  return (size_t)2 * 32 * ((64 * ntq + 4) + PJ_LDX) * sizeof(unsigned int);
-}
-static inline int project_splits_for(int64_t m, int64_t n, int l) {
-  const int ntq = project_ntq_for(l);
-  const int64_t tiles = ceil_div64(n, PJ_BN) * ceil_div64(l, 64 * ntq);
-  int64_t s = std::max<int64_t>(1, 512 / std::max<int64_t>(1, tiles));
-  s = std::min<int64_t>(s, std::max<int64_t>(1, m / 256));
-  return (int)std::min<int64_t>(s, 64);
+// V tile blockIdx.y = sum of the partial tiles that cover it, in workgroup order; a thread owns
+// groups of 4 consecutive columns.  The workgroup range of the tile is uniform per block.
+__global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
+  const int64_t tile = blockIdx.y;
+  const int64_t lo_item = tile * g.slabs, hi_item = lo_item + g.slabs;
+  // first workgroup whose share [items w / wgs, items (w+1) / wgs) reaches into the tile
+  int64_t w_lo = lo_item * g.wgs / g.items;
+  while (g.items * (w_lo + 1) / g.wgs <= lo_item) ++w_lo;
+  int64_t w_hi = w_lo;                               // exclusive
+  while (w_hi < g.wgs && g.items * w_hi / g.wgs < hi_item) ++w_hi;
+  const int64_t tile_floats = (int64_t)g.bmq * g.bnx;
+  const int qb = (int)(tile / g.col_blocks), cb = (int)(tile - (int64_t)qb * g.col_blocks);
+  const int bnx4 = g.bnx >> 2;
+  const int groups = g.bmq * bnx4;
+  for (int e = blockIdx.x * 256 + threadIdx.x; e < groups; e += gridDim.x * 256) {
+    const int qw = e / bnx4, cw = (e - qw * bnx4) << 2;
+    const int64_t q = (int64_t)qb * g.bmq + qw, col = (int64_t)cb * g.bnx + cw;
+    if (q >= g.l || col >= g.n) continue;
+    f32x4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
+    for (int64_t w = w_lo; w < w_hi; w += 8) {
+      // eight partial tiles at a time: loads first (an unused slot re-reads a valid one), then the
+      // additions in workgroup order
+      f32x4 v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) {
+        const int64_t wu = (w + u < w_hi) ? w + u : w;
+        const int64_t first_tile = (g.items * wu / g.wgs) / g.slabs;
+        v[u] = *(const f32x4*)(g.part + (wu * g.segs_max + (tile - first_tile)) * tile_floats +
+                               (int64_t)qw * g.bnx + cw);
+      }
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (w + u < w_hi) s4 += v[u];
+    }
+    if (g.out_ek == EK_F32) {
+      *(f32x4*)((float*)g.V + q * g.n + col) = s4;
+    } else {
+      bf16x4 o;
+#pragma unroll
+      for (int u = 0; u < 4; ++u) o[u] = (bf16_t)s4[u];
+      *(bf16x4*)((bf16_t*)g.V + q * g.n + col) = o;
+    }
+  }
 }
 
-template <int NTQ>
-static int launch_project_ntq(hipStream_t s, const ProjectArgs& g, dim3 grid, const char* name) {
+// Tile shape and ring depth.  Up to 128 columns of Q: 128-column tiles with a two-stage ring, so
+// that two workgroups share a CU (one hides the other's waits) and the partial tiles stay small.
+// Wider Q: one workgroup per CU with a three-stage ring.
+static inline void project_shape_for(int l, int* ntq, int* ntx, int* stages) {
+  if (l <= 64) { *ntq = 1; *ntx = 2; *stages = 2; }
+  else if (l <= 128) { *ntq = 2; *ntx = 2; *stages = 2; }
+  else { *ntq = 4; *ntx = 2; *stages = 3; }
+}
+static size_t project_lds_bytes(int ntq, int ntx, int stages) {
+  return (size_t)stages * SB_BK * 64 * (ntq + ntx) * 2;
+}
+// Fills in the work split of a projection (everything the kernels derive their indexing from).
+static void project_plan(ProjectArgs* g) {
+  int ntq, ntx, stages;
+  project_shape_for(g->l, &ntq, &ntx, &stages);
+  g->bmq = 64 * ntq;
+  g->bnx = 64 * ntx;
+  g->slabs = (int)ceil_div64(g->m, SB_BK);
+  g->col_blocks = (int)ceil_div64(g->n, g->bnx);
+  const int64_t tiles = (int64_t)g->col_blocks * ceil_div64(g->l, g->bmq);
+  g->items = tiles * g->slabs;
+  const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)project_lds_bytes(ntq, ntx, stages)));
+  // at least 4 slabs per workgroup: a partial tile costs as much as a slab to write and sum
+  int64_t wgs = std::min<int64_t>(256 * per_cu, ceil_div64(g->items, 4));
+  wgs = std::max<int64_t>(1, std::min<int64_t>(wgs, g->items));
+  g->wgs = (int)wgs;
+  // a share of ceil(items / wgs) consecutive items touches at most this many output tiles
+  g->segs_max = (int)(ceil_div64(ceil_div64(g->items, wgs), g->slabs) + 1);
+}
+static size_t project_part_floats(int64_t m, int64_t n, int l) {
+  ProjectArgs g;
+  g.m = m; g.n = n; g.l = l;
+  project_plan(&g);
+  return (size_t)g.wgs * g.segs_max * g.bmq * g.bnx;
+}
+
+template <int NTQ, int NTX, int STAGES>
+static int launch_project_shape(hipStream_t s, const ProjectArgs& g, const char* name) {
   static bool attr_done = false;
-  const size_t lds = project_lds_bytes(NTQ);
+  const size_t lds = project_lds_bytes(NTQ, NTX, STAGES);
   if (lds > 64 * 1024 && !attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ>,
+    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(project LDS)");
     attr_done = true;
   }
-  LORACT_LAUNCH(name, s, project_mfma_kernel<NTQ>, grid, dim3(256), lds, g);
+  LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES>), dim3((unsigned)g.wgs), dim3(256), lds, g);
   return LORACT_OK;
 }
 
-// part: splits * l * n floats.
+static int launch_project_main(hipStream_t s, const ProjectArgs& g, const char* name) {
+  if (g.l <= 64) return launch_project_shape<1, 2, 2>(s, g, name);
+  if (g.l <= 128) return launch_project_shape<2, 2, 2>(s, g, name);
+  return launch_project_shape<4, 2, 3>(s, g, name);
+}
+static int launch_project_sum(hipStream_t s, const ProjectArgs& g) {
+  const int64_t tiles = (int64_t)g.col_blocks * ceil_div64(g.l, g.bmq);
+  const int groups = g.bmq * (g.bnx >> 2);
+  // enough blocks per tile to occupy the machine, each thread at least one group
+  int bx = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(groups, 256), ceil_div64(2048, tiles)));
+  LORACT_LAUNCH("project_sum", s, project_sum_kernel, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, g);
+  return LORACT_OK;
+}
+
+// Requires 16-byte aligned rows of Q, X and V (l, ldq, ldx, n multiples of 8; checked by the
+// caller); part: project_part_floats(m, n, l) floats.
 static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = "project") {
-  const int ntq = project_ntq_for(g.l);
-  int64_t rps = ceil_div64(ceil_div64(g.m, g.splits), SB_BK) * SB_BK;
-  g.splits = (int)ceil_div64(g.m, rps);
-  g.rows_per_split = rps;
-  dim3 grid((unsigned)ceil_div64(g.n, PJ_BN), (unsigned)ceil_div64(g.l, 64 * ntq), (unsigned)g.splits);
-  int rc;
-  switch (ntq) {
-    case 1: rc = launch_project_ntq<1>(s, g, grid, name); break;
-    case 2: rc = launch_project_ntq<2>(s, g, grid, name); break;
-    default: rc = launch_project_ntq<4>(s, g, grid, name); break;
-  }
+  project_plan(&g);
+  int rc = launch_project_main(s, g, name);
   if (rc != LORACT_OK) return rc;
-  return launch_sum_partials(s, g.part, g.splits, g.l, g.n, g.n, g.V, g.n, g.out_ek);
+  return launch_project_sum(s, g);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -564,9 +683,6 @@ struct ReconArgs {
   int64_t items;         // column blocks * row_tiles
 };
 
-// Workgroup barrier that first waits for this wave's LDS traffic but leaves vector-memory
-// operations (asynchronous copies, stores) in flight.
-__device__ inline void sb_barrier_lds() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 
 template <int NKS>   // number of 16-deep K steps = ceil(k / 16)
 __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
