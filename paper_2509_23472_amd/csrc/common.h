@@ -121,6 +121,17 @@ __device__ inline void sb_async16(const void* gsrc, void* lds_wave_base) {
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 0);
 }
+// The same copy with the non-temporal cache policy, for operands that are streamed once (the
+// activation matrix): their lines are the first to leave L2, which keeps the small operands that
+// every workgroup re-reads (sampled rows, Q, U) resident there.
+#ifndef SB_STREAM_POLICY
+#define SB_STREAM_POLICY 2    // "nt" bit of the gfx940+ cache-policy operand
+#endif
+__device__ inline void sb_async16_stream(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0,
+                                   SB_STREAM_POLICY);
+}
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding).
 #define SB_WAIT_VMCNT(n) \
   __builtin_amdgcn_s_waitcnt(((n) & 15) | ((((n) >> 4) & 3) << 14) | (7 << 4) | (15 << 8))

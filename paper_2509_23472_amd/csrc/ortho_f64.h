@@ -16,7 +16,7 @@
 
 #define OF_NB 16
 #ifndef GRAM_TARGET_WGS
-#define GRAM_TARGET_WGS 384
+#define GRAM_TARGET_WGS 256
 #endif
 #ifndef CHOL_LDS_THREADS
 #define CHOL_LDS_THREADS 256
@@ -91,8 +91,7 @@ __global__ __launch_bounds__(256) void gram_mfma_kernel(GramArgs g) {
   // branch, where it is waited for on the spot.
   const float ma0 = a_ok0 ? 1.0f : 0.0f, ma1 = a_ok1 ? 1.0f : 0.0f;
   const float mb0 = b_ok0 ? 1.0f : 0.0f, mb1 = b_ok1 ? 1.0f : 0.0f;
-  // They are issued one trip ahead of the 16 matrix instructions that consume them.
-  float fa0[2][4], fa1[2][4], fb0[2][4], fb1[2][4];
+  float fa0[4][4], fa1[4][4], fb0[4][4], fb1[4][4];
   auto load_trip = [&](int64_t r0, float* pa0, float* pa1, float* pb0, float* pb1) {
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
@@ -120,13 +119,15 @@ __global__ __launch_bounds__(256) void gram_mfma_kernel(GramArgs g) {
       acc[1][1] = mfma_f64(a1, b1, acc[1][1]);
     }
   };
-  if (r_begin < r_end) load_trip(r_begin, fa0[0], fa1[0], fb0[0], fb1[0]);
-  for (int64_t r0 = r_begin; r0 < r_end; r0 += 32) {
-    if (r0 + 16 < r_end) load_trip(r0 + 16, fa0[1], fa1[1], fb0[1], fb1[1]);
-    mac_trip(r0, fa0[0], fa1[0], fb0[0], fb1[0]);
-    if (r0 + 16 < r_end) {
-      if (r0 + 32 < r_end) load_trip(r0 + 32, fa0[0], fa1[0], fb0[0], fb1[0]);
-      mac_trip(r0 + 16, fa0[1], fa1[1], fb0[1], fb1[1]);
+  // ring of 4 trips: the loads run 3 trips (48 rows) ahead of the matrix instructions.  Loads past
+  // the end of the chunk are harmless (clamped addresses) and are not multiplied.
+#pragma unroll
+  for (int p = 0; p < 3; ++p) load_trip(r_begin + 16 * p, fa0[p], fa1[p], fb0[p], fb1[p]);
+  for (int64_t r0 = r_begin; r0 < r_end; r0 += 64) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      load_trip(r0 + 16 * (q + 3), fa0[(q + 3) & 3], fa1[(q + 3) & 3], fb0[(q + 3) & 3], fb1[(q + 3) & 3]);
+      if (r0 + 16 * q < r_end) mac_trip(r0 + 16 * q, fa0[q], fa1[q], fb0[q], fb1[q]);
     }
   }
   double* out = g.part + ((int64_t)blockIdx.x * gridDim.y + blockIdx.y) * 4096;
@@ -713,9 +714,13 @@ __global__ __launch_bounds__(256) void ns_finalize_kernel(const float* Q1, const
 // Host-side launchers.
 
 static int gram_rows_per_chunk(int64_t m, int nblocks) {
-  // aim for ~384 workgroups, at least 32 rows per chunk, at most 128 chunks
-  int64_t chunks = std::max<int64_t>(1, GRAM_TARGET_WGS / std::max(1, nblocks));
-  chunks = std::min<int64_t>(chunks, 128);
+  // Whole multiples of the 256 CUs (a workgroup's four waves fill the four SIMDs of a CU), so
+  // that no CU ends up with one workgroup more than its neighbour: one per CU for short
+  // matrices, where the partial blocks are the cost, two for long ones.  At least 32 rows per
+  // chunk, at most 256 chunks.
+  const int64_t target = m >= 32768 ? 2 * GRAM_TARGET_WGS : GRAM_TARGET_WGS;
+  int64_t chunks = std::max<int64_t>(1, target / std::max(1, nblocks));
+  chunks = std::min<int64_t>(chunks, 256);
   int64_t rows = ceil_div64(m, chunks);
   rows = std::max<int64_t>(32, ceil_div64(rows, 16) * 16);
   return (int)rows;

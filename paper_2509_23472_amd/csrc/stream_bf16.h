@@ -118,6 +118,7 @@ struct SketchArgs {
   int splits;
   int64_t k_per_split;   // multiple of SB_BK
   const int32_t* run_flag;   // optional: the launch does nothing when *run_flag == 0
+  int stream_x;              // set by the launcher: X is too large to stay cached, copy it non-temporally
 };
 
 template <int NT, int STAGES>
@@ -167,7 +168,10 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
     if (pos >= nslab) pos -= nslab;
     const int64_t koff = (int64_t)pos * SB_BK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) sb_async16(a_src[i] + koff, st + (wave * 4 + i) * 1024);
+    for (int i = 0; i < 4; ++i) {
+      if (g.stream_x) sb_async16_stream(a_src[i] + koff, st + (wave * 4 + i) * 1024);
+      else sb_async16(a_src[i] + koff, st + (wave * 4 + i) * 1024);
+    }
 #pragma unroll
     for (int i = 0; i < 2 * NT; ++i)
       sb_async16(b_src[i] + koff, st + A_BYTES + (wave * 2 * NT + i) * 1024);
@@ -250,6 +254,10 @@ static inline int sketch_splits_for(int64_t m, int64_t n, int kp) {
   return (int)std::min<int64_t>(s, 16);
 }
 
+// A matrix of this many bytes does not survive in the 256 MB memory-side cache between two
+// passes, so caching its lines only evicts the small operands that are re-read.
+static inline int sb_streams_past_cache(int64_t bytes) { return bytes >= ((int64_t)192 << 20); }
+
 static inline bool sb_aligned(const void* p, int64_t ld) {
   return (((uintptr_t)p) % 16 == 0) && (ld % 8 == 0);
 }
@@ -274,6 +282,7 @@ static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const
 static int launch_sketch_mfma(hipStream_t s, SketchArgs g, const char* name = "sketch",
                               bf16_t* split_out = nullptr) {
   const int nt = sketch_nt_for(g.kp);
+  g.stream_x = sb_streams_past_cache(g.m * g.n * 2);
   int64_t kps = ceil_div64(ceil_div64(g.n, g.splits), SB_BK) * SB_BK;
   g.splits = (int)ceil_div64(g.n, kps);
   g.k_per_split = kps;
@@ -360,6 +369,7 @@ struct ProjectArgs {
   int wgs;                 // workgroups sharing the items
   int segs_max;            // partial tiles reserved per workgroup
   int bmq, bnx;            // rows and columns of an output tile
+  int stream_x;            // X is too large to stay cached: copy it non-temporally
 };
 
 typedef short s16x4 __attribute__((ext_vector_type(4)));
@@ -429,7 +439,10 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(ProjectArgs g) {
         int64_t grow = r0 + row;
         if (grow > g.m - 1) grow = g.m - 1;
         if (col0 + ch * 8 + 8 <= g.n && !PJ_SKIPPED(1))
-          sb_async16(x_col + grow * g.ldx + ch * 8, st + (wave * 2 * NTX + i) * 1024);
+        {
+          if (g.stream_x) sb_async16_stream(x_col + grow * g.ldx + ch * 8, st + (wave * 2 * NTX + i) * 1024);
+          else sb_async16(x_col + grow * g.ldx + ch * 8, st + (wave * 2 * NTX + i) * 1024);
+        }
       }
 #pragma unroll
       for (int i = 0; i < 2 * NTQ; ++i) {
@@ -639,6 +652,7 @@ static int launch_project_sum(hipStream_t s, const ProjectArgs& g) {
 // caller); part: project_part_floats(m, n, l) floats.
 static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = "project") {
   project_plan(&g);
+  g.stream_x = sb_streams_past_cache(g.m * g.n * 2);
   int rc = launch_project_main(s, g, name);
   if (rc != LORACT_OK) return rc;
   return launch_project_sum(s, g);
@@ -681,6 +695,7 @@ struct ReconArgs {
   int64_t ldxh;
   int row_tiles;         // ceil(m / 64)
   int64_t items;         // column blocks * row_tiles
+  int stream_out;        // Xhat is too large to stay cached: store it non-temporally
 };
 
 
@@ -834,7 +849,10 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
         const int row = e >> 4, ch = e & 15;
         const int64_t grow = r0 + row, col = col0 + ch * 8;
         if (grow < g.m && col + 8 <= g.n && !(RC_SKIPPED(2) && it > 0))
-          *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = o[q];
+        {
+          if (g.stream_out) __builtin_nontemporal_store(o[q], (bf16x8*)(g.Xhat + grow * g.ldxh + col));
+          else *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = o[q];
+        }
       }
     }
   }
@@ -863,6 +881,7 @@ static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) 
 // Requires k % 8 == 0 and 16-byte aligned U, V, Xhat rows (checked by the caller).
 static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
   const int nks = (g.k + 15) / 16;
+  g.stream_out = sb_streams_past_cache(g.m * g.n * 2);
   g.row_tiles = (int)ceil_div64(g.m, RC_BM);
   g.items = ceil_div64(g.n, RC_BN) * g.row_tiles;
   // as many workgroups as stay resident: LDS allows 160 KB per CU, registers about 2 per CU
