@@ -153,7 +153,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "c5stream"])
+    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "coherent", "c5stream"])
     ap.add_argument("--layers", type=int, default=2,
                     help="c5stream only: decoder layers to stream (7 sites each; the full config is 32)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -361,7 +361,18 @@ def main() -> int:
         rprof = L.loract_profile_end()
         us_trunc = sum(ms for nm, (ms, cnt) in rprof.items()
                        if nm in ("jacobi_eig", "truncate_bbt", "truncate_qw", "truncate_wtb")) * 1e3 / rsteps
+        ur, vr = L.loract_rsvd(x, k, oversample=8, power_iters=1, seed=w.seed)
+        xr = L.loract_reconstruct(ur, vr)
+        err_rsvd = float((torch.linalg.norm(xr.float() - x.float()) / torch.linalg.norm(x.float())).item())
+        ur0, vr0 = L.loract_rsvd(x, k, oversample=0, power_iters=0, seed=w.seed)
+        xr0 = L.loract_reconstruct(ur0, vr0)
+        err_rsvd0 = float((torch.linalg.norm(xr0.float() - x.float()) / torch.linalg.norm(x.float())).item())
+        del ur, vr, xr, ur0, vr0, xr0
         comparator = {"method": "rsvd (oversampling 8, 1 power iteration, rank %d)" % k,
+                      "rel_fro_err_rsvd": round(err_rsvd, 6),
+                      "rel_fro_err_rsvd_plain": round(err_rsvd0, 6),
+                      "note_err": "rsvd_plain = Gaussian test matrix of k columns, no power iteration: "
+                                  "the method Algorithm 1 differs from only in the test matrix",
                       "total_us": round(us_rsvd, 1), "truncation_us": round(us_trunc, 1),
                       "range_finder_us": round(us_rsvd - us_trunc, 1),
                       "loract_compress_us": round(us_c, 1),
@@ -386,6 +397,8 @@ def main() -> int:
         "hbm_frac_two_pass": round((2 * x_bytes + k * n * b + 2 * m * k * 4 + 2 * (m + n) * k * b + x_bytes)
                                    / ((us_c + us_r) * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
         "rel_fro_err": round(err, 6),
+        "rel_fro_err_rank_k_floor": (round(float(w.extras["rank_k_floor"]), 6)
+                                     if "rank_k_floor" in w.extras else None),
         "roofline": roofline,
         "roofline_streaming": roofline_streaming,
         "comparator": comparator,

@@ -96,3 +96,35 @@ def test_c4_rsvd_comparator():
     torch.cuda.synchronize()
     e_loract = orc.rel_fro(to_host(ul) @ to_host(vl), w.x.astype(np.float64))
     print("quality: loract %.4e  rsvd %.4e" % (e_loract, res["quality_gpu"]))
+
+
+def test_coherent_workload_sampling_versus_gaussian():
+    # Second workload (outlier tokens with directions of their own, coherence at its maximum):
+    # parity of both methods with the oracle, and the measured gap between row sampling and a
+    # Gaussian test matrix at equal rank.  Theorem 4.3 ties the sampling error to the coherence but
+    # the paper prints no number, so the gap is reported, not asserted; what is asserted is that
+    # GPU and oracle agree on each method's loss and that more sampled rows (l = 2k) do not hurt.
+    import paper_2509_23472_amd as L
+    w = synth.coherent_activations(m=4096, n=1024, k=64, seed=6)
+    x64 = w.x.astype(np.float64)
+    x = to_device(w.x, w.dtype)
+    status = torch.full((1,), -1, dtype=torch.int32, device="cuda")
+    u, v = L.loract_compress(x, w.k, seed=w.seed, status=status)
+    ur, vr = L.loract_rsvd(x, w.k, oversample=0, power_iters=0, seed=w.seed)
+    torch.cuda.synchronize()
+    res = check_compress_parity(w, u, v)
+    omega_t = synth.round_to_bf16(orc.gaussian_omega_t(w.k, w.n, w.seed).astype(np.float32))
+    uo, vo = orc.rsvd(x64, w.k, omega_t=omega_t.astype(np.float64))
+    res_r = check_compress_parity(w, ur, vr, oracle_factors=(uo, vo))
+    print("coherent: sampling %.4e (oracle %.4e)  gaussian %.4e (oracle %.4e)  status %d" % (
+        res["quality_gpu"], res["quality_oracle"], res_r["quality_gpu"], res_r["quality_oracle"],
+        int(status.item())))
+    # both sides agree on how much each method loses
+    assert abs(res["quality_gpu"] - res["quality_oracle"]) <= 5e-3 * max(1.0, res["quality_oracle"])
+    assert abs(res_r["quality_gpu"] - res_r["quality_oracle"]) <= 5e-3 * max(1.0, res_r["quality_oracle"])
+    # more sampled rows (Theorem 4.3's l) close part of the gap
+    u2, v2 = L.loract_compress(x, w.k, seed=w.seed, l=2 * w.k)
+    torch.cuda.synchronize()
+    e2 = orc.rel_fro(to_host(u2) @ to_host(v2), x64)
+    print("coherent: sampling with l = 2k: %.4e" % e2)
+    assert e2 <= res["quality_gpu"] * 1.02

@@ -72,6 +72,19 @@ def spectrum_matrix(m: int, n: int, s: np.ndarray, noise: float, seed: int,
     return x
 
 
+def spectrum_rank_k_floor(m: int, n: int, s: np.ndarray, noise: float, k: int,
+                          p_max: int = 1024) -> float:
+    """What the generator's own spectrum says a rank-k approximation of `spectrum_matrix(...)`
+    can reach, relative to ||X||_F: cutting the signal after k terms leaves
+    sqrt(c^2 sum_{i>k} s_i^2 + noise^2 m n), an upper bound on (and, the noise being far below
+    the kept terms, an estimate of) the Eckart-Young optimum.  Expected values over the noise."""
+    p = int(min(m, n, len(s), p_max))
+    s = np.asarray(s[:p], dtype=np.float64)
+    c2 = float(m) * float(n) / float(np.sum(s * s))
+    noise2 = noise * noise * float(m) * float(n)
+    return float(np.sqrt((c2 * np.sum(s[k:] ** 2) + noise2) / (c2 * np.sum(s * s) + noise2)))
+
+
 def low_rank_plus_noise(m: int, n: int, rank: int, noise: float, seed: int) -> np.ndarray:
     """X = A B + noise * N with A (m x rank), B (rank x n), N all i.i.d. N(0,1) (float64)."""
     rng = np.random.default_rng(seed)
@@ -134,7 +147,8 @@ def c2_vit(m: int = 64 * 197, n: int = 768, k: int = 32, seed: int = 2) -> Workl
     """
     s = 0.9 ** np.arange(768)
     return _finish("c2_vit_%dx%d_k%d" % (m, n, k),
-                   spectrum_matrix(m, n, s, 1e-3, seed), "bf16", k, seed)
+                   spectrum_matrix(m, n, s, 1e-3, seed), "bf16", k, seed,
+                   rank_k_floor=spectrum_rank_k_floor(m, n, s, 1e-3, k))
 
 
 def c3_llama(m: int = 4 * 2048, n: int = 4096, k: int = 128, seed: int = 3,
@@ -152,7 +166,8 @@ def c3_llama(m: int = 4 * 2048, n: int = 4096, k: int = 128, seed: int = 3,
     b = round_to_bf16((rng.standard_normal((r_lora, n_out)) / np.sqrt(r_lora)).astype(np.float32))
     return _finish("c3_llama_%dx%d_k%d" % (m, n, k),
                    spectrum_matrix(m, n, s, 1e-3, seed), "bf16", k, seed,
-                   dY=dy, B_lora=b, r_lora=r_lora, scale=1.0)
+                   dY=dy, B_lora=b, r_lora=r_lora, scale=1.0,
+                   rank_k_floor=spectrum_rank_k_floor(m, n, s, 1e-3, k))
 
 
 def c4_mlp(m: int = 4 * 2048, n: int = 11008, k: int = 256, seed: int = 4,
@@ -164,7 +179,8 @@ def c4_mlp(m: int = 4 * 2048, n: int = 11008, k: int = 256, seed: int = 4,
     s = np.exp(-np.arange(n, dtype=np.float64) / 64.0)
     return _finish("c4_mlp_%dx%d_k%d" % (m, n, k),
                    spectrum_matrix(m, n, s, 1e-3, seed), "bf16", k, seed,
-                   oversample=oversample, power_iters=power_iters)
+                   oversample=oversample, power_iters=power_iters,
+                   rank_k_floor=spectrum_rank_k_floor(m, n, s, 1e-3, k))
 
 
 def c5_site_seed(layer: int, site: int) -> int:
@@ -185,6 +201,31 @@ def c5_long_context_site(layer: int = 0, site: int = 0, m: int = 16 * 4096,
     s = np.arange(1, n + 1, dtype=np.float64) ** -1.5
     return _finish("c5_L%d_S%d_%dx%d_k%d" % (layer, site, m, n, k),
                    spectrum_matrix(m, n, s, 1e-3, seed), "bf16", k, seed)
+
+
+def coherent_activations(m: int = 8192, n: int = 4096, k: int = 128, seed: int = 6,
+                         outlier_rows: int = 8, outlier_scale: float = 100.0,
+                         dtype: str = "bf16") -> Workload:
+    """Second workload: activations with outlier tokens (Section 2 reports a leading singular
+    value above 1e4 against a bulk of 1e0..1e2; Theorem 4.3 ties the sampling error to the
+    coherence of the leading singular vectors).
+
+    The config-3 recipe plus `outlier_rows` seeded rows that each receive their own direction:
+    row r_j += outlier_scale * sqrt(n) * w_j with w_j a random unit vector, i.e. `outlier_scale`
+    times the RMS row norm of the bulk in a direction no other row shares.  The leading singular
+    vectors then sit on single rows (coherence at its maximum m/k) and the leading singular values
+    are ~outlier_scale times the bulk's.  Uniform row sampling sees such a row with probability
+    k/m only and cannot recover its direction from the others, which is the regime where it is
+    expected to lose against a Gaussian test matrix.  extras: the outlier row ids.
+    """
+    s = np.arange(1, min(m, n) + 1, dtype=np.float64) ** -1.5
+    x = spectrum_matrix(m, n, s, 1e-3, seed)
+    rng = np.random.default_rng(seed + 1000)
+    rows = np.sort(rng.choice(m, size=outlier_rows, replace=False))
+    w = rng.standard_normal((outlier_rows, n))
+    w /= np.linalg.norm(w, axis=1, keepdims=True)
+    x[rows, :] += outlier_scale * np.sqrt(n) * w
+    return _finish("coherent_%dx%d_k%d" % (m, n, k), x, dtype, k, seed, outlier_rows=rows)
 
 
 def exact_rank(m: int, n: int, rank: int, seed: int, dtype: str = "f32") -> Workload:
@@ -208,4 +249,5 @@ FULL_SIZE: Dict[str, Callable[[], Workload]] = {
     "c3": c3_llama,
     "c4": c4_mlp,
     "c5": c5_long_context_site,
+    "coherent": coherent_activations,
 }
