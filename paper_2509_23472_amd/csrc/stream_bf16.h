@@ -121,17 +121,20 @@ struct SketchArgs {
   int stream_x;              // set by the launcher: X is too large to stay cached, copy it non-temporally
 };
 
-template <int NT, int STAGES>
-__global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
-  constexpr int BN = 64 * NT;
-  constexpr int A_BYTES = SB_BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
-  constexpr int LOADS = 4 + 2 * NT;     // wave-level copy instructions per slab per wave
+// WM = 64-row wave groups per workgroup: 2 (4 waves, 128 rows) or 4 (8 waves, 256 rows; halves the
+// re-reads of Bt per row of X, for matrices tall enough to fill the CUs with 256-row tiles).
+template <int NT, int STAGES, int WM>
+__global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
+  constexpr int BM = 64 * WM, BN = 64 * NT;
+  constexpr int NB = 4 * NT / WM;       // Bt copy instructions per wave per slab
+  constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
+  constexpr int LOADS = 4 + NB;         // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
   if (g.run_flag && *g.run_flag == 0) return;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
-  const int64_t row0 = (int64_t)blockIdx.y * SB_BM;
+  const int64_t row0 = (int64_t)blockIdx.y * BM;
   const int col0 = blockIdx.z * BN;
   // Split z owns a contiguous K range.  Each workgroup walks its slabs starting from a different
   // offset (rotated by its row-tile index): with a power-of-two row pitch, workgroups that all read
@@ -153,10 +156,10 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
     if (r >= g.m) r = g.m - 1;
     a_src[i] = g.X + r * g.ldx + kbeg + kc * 8;
   }
-  const bf16_t* b_src[2 * NT];
+  const bf16_t* b_src[NB];
 #pragma unroll
-  for (int i = 0; i < 2 * NT; ++i) {
-    const int j = col0 + (wave * 2 * NT + i) * 8 + sub;
+  for (int i = 0; i < NB; ++i) {
+    const int j = col0 + (wave * NB + i) * 8 + sub;
     int64_t r = 0;
     if (j < g.l) r = g.b_rows ? (int64_t)g.b_rows[j] : (int64_t)j;
     else r = g.b_rows ? (int64_t)g.b_rows[0] : 0;
@@ -173,8 +176,8 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
       else sb_async16(a_src[i] + koff, st + (wave * 4 + i) * 1024);
     }
 #pragma unroll
-    for (int i = 0; i < 2 * NT; ++i)
-      sb_async16(b_src[i] + koff, st + A_BYTES + (wave * 2 * NT + i) * 1024);
+    for (int i = 0; i < NB; ++i)
+      sb_async16(b_src[i] + koff, st + A_BYTES + (wave * NB + i) * 1024);
   };
 
   f32x16 acc[2][NT];
@@ -237,9 +240,11 @@ __global__ __launch_bounds__(256) void sketch_mfma_kernel(SketchArgs g) {
     }
 }
 
-static inline int sketch_stages_for(int nt) { return nt == 4 ? 3 : 4; }
-static size_t sketch_lds_bytes(int nt) {
-  return (size_t)sketch_stages_for(nt) * (SB_BM + 64 * nt) * 128;
+// Tall matrices with a wide sketch: 256-row tiles (8 waves), as soon as they alone fill the CUs.
+static inline int sketch_wm_for(int64_t m, int nt) { return (nt == 4 && m >= 256 * 256) ? 4 : 2; }
+static inline int sketch_stages_for(int nt, int wm) { return wm == 4 ? 2 : (nt == 4 ? 3 : 4); }
+static size_t sketch_lds_bytes(int nt, int wm) {
+  return (size_t)sketch_stages_for(nt, wm) * (64 * wm + 64 * nt) * 128;
 }
 
 static inline int sketch_nt_for(int kp) { return kp <= 64 ? 1 : (kp <= 128 ? 2 : 4); }
@@ -247,7 +252,8 @@ static inline int sketch_nt_for(int kp) { return kp <= 64 ? 1 : (kp <= 128 ? 2 :
 // Number of K splits: fill ~256-512 workgroups, at least 512 columns per split.
 static inline int sketch_splits_for(int64_t m, int64_t n, int kp) {
   const int nt = sketch_nt_for(kp);
-  const int64_t tiles = ceil_div64(m, SB_BM) * ceil_div64(kp, 64 * nt);
+  const int wm = sketch_wm_for(m, nt);
+  const int64_t tiles = ceil_div64(m, 64 * wm) * ceil_div64(kp, 64 * nt);
   // one workgroup per CU (the multi-stage LDS pipeline fills a CU's LDS), at least 512 columns each
   int64_t s = std::max<int64_t>(1, 256 / std::max<int64_t>(1, tiles));
   s = std::min<int64_t>(s, std::max<int64_t>(1, n / 512));
@@ -262,17 +268,18 @@ static inline bool sb_aligned(const void* p, int64_t ld) {
   return (((uintptr_t)p) % 16 == 0) && (ld % 8 == 0);
 }
 
-template <int NT>
+template <int NT, int WM>
 static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const char* name) {
+  constexpr int STAGES = WM == 4 ? 2 : (NT == 4 ? 3 : 4);
   static bool attr_done = false;
-  const size_t lds = sketch_lds_bytes(NT);
+  const size_t lds = sketch_lds_bytes(NT, WM);
   if (lds > 64 * 1024 && !attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, (NT == 4 ? 3 : 4)>,
+    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, STAGES, WM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(sketch LDS)");
     attr_done = true;
   }
-  LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, (NT == 4 ? 3 : 4)>), grid, dim3(256), lds, g);
+  LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, STAGES, WM>), grid, dim3(128 * WM), lds, g);
   return LORACT_OK;
 }
 
@@ -286,14 +293,15 @@ static int launch_sketch_mfma(hipStream_t s, SketchArgs g, const char* name = "s
   int64_t kps = ceil_div64(ceil_div64(g.n, g.splits), SB_BK) * SB_BK;
   g.splits = (int)ceil_div64(g.n, kps);
   g.k_per_split = kps;
-  dim3 grid((unsigned)g.splits, (unsigned)ceil_div64(g.m, SB_BM), (unsigned)ceil_div64(g.kp, 64 * nt));
+  const int wm = sketch_wm_for(g.m, nt);
+  dim3 grid((unsigned)g.splits, (unsigned)ceil_div64(g.m, 64 * wm), (unsigned)ceil_div64(g.kp, 64 * nt));
   if (grid.y > 65535) return LORACT_ERR_UNSUPPORTED;
   if (split_out && g.splits == 1) g.Y = g.part;     // single split: Y itself is the "partial"
   int rc;
   switch (nt) {
-    case 1: rc = launch_sketch_nt<1>(s, g, grid, name); break;
-    case 2: rc = launch_sketch_nt<2>(s, g, grid, name); break;
-    default: rc = launch_sketch_nt<4>(s, g, grid, name); break;
+    case 1: rc = launch_sketch_nt<1, 2>(s, g, grid, name); break;
+    case 2: rc = launch_sketch_nt<2, 2>(s, g, grid, name); break;
+    default: rc = wm == 4 ? launch_sketch_nt<4, 4>(s, g, grid, name) : launch_sketch_nt<4, 2>(s, g, grid, name); break;
   }
   if (rc != LORACT_OK) return rc;
   if (split_out)
@@ -379,19 +387,22 @@ __device__ inline s16x4 sb_read_tr(const unsigned char* lds_ptr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)lds_ptr);
 }
 
-// Output tile (64 NTQ) x (64 NTX), waves 2 x 2, each with NTQ x NTX matrix-core tiles.
-template <int NTQ, int NTX, int STAGES>
-__global__ __launch_bounds__(256) void project_mfma_kernel(ProjectArgs g) {
-  constexpr int BMQ = 64 * NTQ, BNX = 64 * NTX;
+// Output tile (64 NTQ) x (32 NTX WN), waves 2 x WN, each with NTQ x NTX matrix-core tiles.
+// WN = 4 (8 waves, 256 columns of X for NTX = 2) halves the re-reads of Q per byte of X.
+template <int NTQ, int NTX, int STAGES, int WN>
+__global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
+  constexpr int NW = 2 * WN;                       // waves
+  constexpr int BMQ = 64 * NTQ, BNX = 32 * NTX * WN;
   constexpr int CQ = BMQ / 8, CX = BNX / 8;        // 16-byte chunks per slab row
   constexpr int QPITCH = BMQ * 2, XPITCH = BNX * 2;
   constexpr int X_BYTES = SB_BK * XPITCH, Q_BYTES = SB_BK * QPITCH;
   constexpr int STAGE_BYTES = X_BYTES + Q_BYTES;
-  constexpr int LOADS = 2 * NTQ + 2 * NTX;         // wave-level copy instructions per slab per wave
+  constexpr int XI = CX / NW, QI = CQ / NW;        // copy instructions per wave per slab
+  constexpr int LOADS = XI + QI;
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = wave / WN, wn = wave % WN;
 
   // fragment addresses inside a stage (for K step 0, first half): lane s of a 16-lane group points
   // at row s / 4, columns 4 (s % 4) .. + 3 of the group's 16 columns; lanes 32..63 take rows + 8
@@ -433,25 +444,25 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(ProjectArgs g) {
       unsigned char* st = sb_smem + (sl % STAGES) * STAGE_BYTES;
       const int64_t r0 = (int64_t)(s_beg + sl) * SB_BK;
 #pragma unroll
-      for (int i = 0; i < 2 * NTX; ++i) {
-        const int row = (wave * 2 * NTX + i) * (64 / CX) + lane / CX;
+      for (int i = 0; i < XI; ++i) {
+        const int row = (wave * XI + i) * (64 / CX) + lane / CX;
         const int ch = (lane % CX) ^ (2 * (row & 3));
         int64_t grow = r0 + row;
         if (grow > g.m - 1) grow = g.m - 1;
         if (col0 + ch * 8 + 8 <= g.n && !PJ_SKIPPED(1))
         {
-          if (g.stream_x) sb_async16_stream(x_col + grow * g.ldx + ch * 8, st + (wave * 2 * NTX + i) * 1024);
-          else sb_async16(x_col + grow * g.ldx + ch * 8, st + (wave * 2 * NTX + i) * 1024);
+          if (g.stream_x) sb_async16_stream(x_col + grow * g.ldx + ch * 8, st + (wave * XI + i) * 1024);
+          else sb_async16(x_col + grow * g.ldx + ch * 8, st + (wave * XI + i) * 1024);
         }
       }
 #pragma unroll
-      for (int i = 0; i < 2 * NTQ; ++i) {
-        const int row = (wave * 2 * NTQ + i) * (64 / CQ) + lane / CQ;
+      for (int i = 0; i < QI; ++i) {
+        const int row = (wave * QI + i) * (64 / CQ) + lane / CQ;
         const int ch = (lane % CQ) ^ (2 * (row & 3));
         int64_t grow = r0 + row;
         if (grow > g.m - 1) grow = g.m - 1;
         if (q0 + ch * 8 + 8 <= g.l && !PJ_SKIPPED(1))
-          sb_async16(q_col + grow * g.ldq + ch * 8, st + X_BYTES + (wave * 2 * NTQ + i) * 1024);
+          sb_async16(q_col + grow * g.ldq + ch * 8, st + X_BYTES + (wave * QI + i) * 1024);
       }
     };
 
@@ -511,9 +522,9 @@ __global__ __launch_bounds__(256) void project_mfma_kernel(ProjectArgs g) {
       if (left < SB_BK) {
         // last slab of the matrix: its rows past m (copies of row m - 1) are cleared in LDS
         const u32x4 z = {0u, 0u, 0u, 0u};
-        for (int e = (int)left * (XPITCH / 16) + t; e < SB_BK * (XPITCH / 16); e += 256)
+        for (int e = (int)left * (XPITCH / 16) + t; e < SB_BK * (XPITCH / 16); e += 64 * NW)
           *(u32x4*)(st + e * 16) = z;
-        for (int e = (int)left * (QPITCH / 16) + t; e < SB_BK * (QPITCH / 16); e += 256)
+        for (int e = (int)left * (QPITCH / 16) + t; e < SB_BK * (QPITCH / 16); e += 64 * NW)
           *(u32x4*)(st + X_BYTES + e * 16) = z;
         sb_barrier_lds();
       }
@@ -586,26 +597,29 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
 
 // Tile shape and ring depth.  Up to 128 columns of Q: 128-column tiles with a two-stage ring, so
 // that two workgroups share a CU (one hides the other's waits) and the partial tiles stay small.
-// Wider Q: one workgroup per CU with a three-stage ring.
-static inline void project_shape_for(int l, int* ntq, int* ntx, int* stages) {
+// Wider Q: one workgroup per CU, three stages of 128 columns, or for tall matrices (where the
+// partial tiles are small against X) eight waves on 256 columns with two stages.
+static inline void project_shape_for(int l, int64_t m, int* ntq, int* ntx, int* stages, int* wn) {
+  *wn = 2;
   if (l <= 64) { *ntq = 1; *ntx = 2; *stages = 2; }
   else if (l <= 128) { *ntq = 2; *ntx = 2; *stages = 2; }
-  else { *ntq = 4; *ntx = 2; *stages = 3; }
+  else if (m < 32768) { *ntq = 4; *ntx = 2; *stages = 3; }
+  else { *ntq = 4; *ntx = 2; *stages = 2; *wn = 4; }
 }
-static size_t project_lds_bytes(int ntq, int ntx, int stages) {
-  return (size_t)stages * SB_BK * 64 * (ntq + ntx) * 2;
+static size_t project_lds_bytes(int ntq, int ntx, int stages, int wn) {
+  return (size_t)stages * SB_BK * (64 * ntq + 32 * ntx * wn) * 2;
 }
 // Fills in the work split of a projection (everything the kernels derive their indexing from).
 static void project_plan(ProjectArgs* g) {
-  int ntq, ntx, stages;
-  project_shape_for(g->l, &ntq, &ntx, &stages);
+  int ntq, ntx, stages, wn;
+  project_shape_for(g->l, g->m, &ntq, &ntx, &stages, &wn);
   g->bmq = 64 * ntq;
-  g->bnx = 64 * ntx;
+  g->bnx = 32 * ntx * wn;
   g->slabs = (int)ceil_div64(g->m, SB_BK);
   g->col_blocks = (int)ceil_div64(g->n, g->bnx);
   const int64_t tiles = (int64_t)g->col_blocks * ceil_div64(g->l, g->bmq);
   g->items = tiles * g->slabs;
-  const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)project_lds_bytes(ntq, ntx, stages)));
+  const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)project_lds_bytes(ntq, ntx, stages, wn)));
   // at least 4 slabs per workgroup: a partial tile costs as much as a slab to write and sum
   int64_t wgs = std::min<int64_t>(256 * per_cu, ceil_div64(g->items, 4));
   wgs = std::max<int64_t>(1, std::min<int64_t>(wgs, g->items));
@@ -620,24 +634,25 @@ static size_t project_part_floats(int64_t m, int64_t n, int l) {
   return (size_t)g.wgs * g.segs_max * g.bmq * g.bnx;
 }
 
-template <int NTQ, int NTX, int STAGES>
+template <int NTQ, int NTX, int STAGES, int WN>
 static int launch_project_shape(hipStream_t s, const ProjectArgs& g, const char* name) {
   static bool attr_done = false;
-  const size_t lds = project_lds_bytes(NTQ, NTX, STAGES);
+  const size_t lds = project_lds_bytes(NTQ, NTX, STAGES, WN);
   if (lds > 64 * 1024 && !attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES>,
+    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES, WN>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(project LDS)");
     attr_done = true;
   }
-  LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES>), dim3((unsigned)g.wgs), dim3(256), lds, g);
+  LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES, WN>), dim3((unsigned)g.wgs), dim3(128 * WN), lds, g);
   return LORACT_OK;
 }
 
 static int launch_project_main(hipStream_t s, const ProjectArgs& g, const char* name) {
-  if (g.l <= 64) return launch_project_shape<1, 2, 2>(s, g, name);
-  if (g.l <= 128) return launch_project_shape<2, 2, 2>(s, g, name);
-  return launch_project_shape<4, 2, 3>(s, g, name);
+  if (g.l <= 64) return launch_project_shape<1, 2, 2, 2>(s, g, name);
+  if (g.l <= 128) return launch_project_shape<2, 2, 2, 2>(s, g, name);
+  if (g.m < 32768) return launch_project_shape<4, 2, 3, 2>(s, g, name);
+  return launch_project_shape<4, 2, 2, 4>(s, g, name);
 }
 static int launch_project_sum(hipStream_t s, const ProjectArgs& g) {
   const int64_t tiles = (int64_t)g.col_blocks * ceil_div64(g.l, g.bmq);
