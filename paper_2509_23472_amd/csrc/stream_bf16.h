@@ -690,11 +690,8 @@ static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = 
 // U tile layout in LDS: [row][2 NKS chunks of 16 bytes], chunk c of row r stored at position
 // (c + r) mod 2 NKS, which spreads the fragment reads of consecutive rows over the banks.
 
-#define RC_BN 128
 #define RC_BM 64
-#define RC_LDV (RC_BN + 4)   // words per pair-row of the V tile
-#define RC_LDC (RC_BN + 8)   // bf16 elements per row of the output staging tile
-#define RC_CS_BYTES (RC_BM * RC_LDC * 2)
+#define RC_LDV (128 + 4)     // words per pair-row of the V staging tile (128 columns at a time)
 #ifdef RC_ABLATE   // development harness only: bit 0 skips the U copies, bit 1 most stores, bit 2 the products
 #define RC_SKIPPED(bit) ((RC_ABLATE) & (bit))
 #else
@@ -710,22 +707,36 @@ struct ReconArgs {
   int64_t ldxh;
   int row_tiles;         // ceil(m / 64)
   int64_t items;         // column blocks * row_tiles
+  int bn;                // columns per block
   int stream_out;        // Xhat is too large to stay cached: store it non-temporally
 };
 
 
-template <int NKS>   // number of 16-deep K steps = ceil(k / 16)
+// NKS = number of 16-deep K steps = ceil(k / 16).  Four waves.  WIDE = false: 128 columns per
+// block, waves 2 (64-column groups) x 2 (32-row halves).  WIDE = true (for k > 128, where a
+// workgroup fills a CU's LDS anyway): 256 columns per block, one 64-column group per wave and both
+// row halves -- half the U traffic and half the barriers per byte written, and every U fragment
+// feeds four matrix instructions instead of two.
+template <int NKS, bool WIDE>
 __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
+  constexpr int NW = 4, NT = 256;               // waves, threads
+  constexpr int WN = WIDE ? 4 : 2;              // 64-column groups
+  constexpr int RH = WIDE ? 2 : 1;              // 32-row halves per wave
+  constexpr int NST = 2 * WN;                   // 16-byte stores per thread and tile
+  constexpr int BN = 64 * WN;
+  constexpr int LDC = BN + 8;                   // bf16 elements per row of the output staging tile
+  constexpr int CS_BYTES = RC_BM * LDC * 2;
   constexpr int CPR = 2 * NKS;                  // 16-byte chunks per U row in LDS
   constexpr int UBUF = RC_BM * CPR * 16;        // bytes per U buffer = CPR wave-wide copies
-  constexpr int NCOPY_MIN = CPR / 4;            // fewest copy instructions any wave issues per tile
+  constexpr int NCOPY_MIN = CPR / NW;           // fewest copy instructions any wave issues per tile
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
-  bf16_t* Cs = (bf16_t*)sb_smem;                                   // [64][RC_LDC]
-  unsigned char* Ub = sb_smem + RC_CS_BYTES;                       // 2 x UBUF
+  bf16_t* Cs = (bf16_t*)sb_smem;                                   // [64][LDC]
+  unsigned char* Ub = sb_smem + CS_BYTES;                          // 2 x UBUF
   unsigned int* Vs = (unsigned int*)sb_smem;                       // [NKS * 8][RC_LDV], prologue only
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = wave >> 1, wn = wave & 1;
+  const int wm = WIDE ? wave : wave >> 1;       // 64-column group
+  const int wn = WIDE ? 0 : wave & 1;           // first 32-row half
   const int cvalid = g.k >> 3;                  // valid chunks per row (k is a multiple of 8)
   const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
                         (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f};
@@ -734,8 +745,8 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
   auto issue_copy = [&](int rt, int buf) {
     const int64_t r0 = (int64_t)rt * RC_BM;
 #pragma unroll
-    for (int i = 0; i < (CPR + 3) / 4; ++i) {
-      const int ins = wave + 4 * i;
+    for (int i = 0; i < (CPR + NW - 1) / NW; ++i) {
+      const int ins = wave + NW * i;
       if (ins < CPR) {
         const int p = ins * 64 + lane;
         const int row = p / CPR, pos = p % CPR;
@@ -759,30 +770,35 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
     const int64_t rt_stop = rt_first + (item_end - item);
     const int rt_last = (int)(rt_stop < g.row_tiles ? rt_stop : g.row_tiles);   // exclusive
     item += rt_last - rt_first;
-    const int64_t col0 = cb * RC_BN;
+    const int64_t col0 = cb * BN;
 
-    __syncthreads();   // a previous segment is done with LDS (and its stores have been issued)
-    for (int c = t; c < NKS * 8 * 16; c += 256) {
-      const int p = c >> 4, ch = c & 15;
-      const int64_t col = col0 + ch * 8;
-      const bool cok = col + 8 <= g.n;
-      const bf16_t* src = g.V + (int64_t)(2 * p) * g.n + col;
-      const bf16x8 lo = (cok && 2 * p < g.k) ? *(const bf16x8*)src : zero8;
-      const bf16x8 hi = (cok && 2 * p + 1 < g.k) ? *(const bf16x8*)(src + g.n) : zero8;
-      u32x4 w0, w1;
-      sb_interleave(lo, hi, &w0, &w1);
-      unsigned int* d = Vs + p * RC_LDV + ch * 8;
-      *(u32x4*)d = w0;
-      *(u32x4*)(d + 4) = w1;
-    }
-    __syncthreads();
-    // this wave's V fragments: 64 columns of Xhat, all K steps
+    // this wave's V fragments (64 columns of Xhat, all K steps), staged 128 columns at a time
     bf16x8 a[NKS][2];
 #pragma unroll
-    for (int ks = 0; ks < NKS; ++ks)
+    for (int h = 0; h < WN / 2; ++h) {
+      __syncthreads();   // LDS is free: a previous segment (or half) is done with it
+      for (int c = t; c < NKS * 8 * 16; c += NT) {
+        const int p = c >> 4, ch = c & 15;
+        const int64_t col = col0 + 128 * h + ch * 8;
+        const bool cok = col + 8 <= g.n;
+        const bf16_t* src = g.V + (int64_t)(2 * p) * g.n + col;
+        const bf16x8 lo = (cok && 2 * p < g.k) ? *(const bf16x8*)src : zero8;
+        const bf16x8 hi = (cok && 2 * p + 1 < g.k) ? *(const bf16x8*)(src + g.n) : zero8;
+        u32x4 w0, w1;
+        sb_interleave(lo, hi, &w0, &w1);
+        unsigned int* d = Vs + p * RC_LDV + ch * 8;
+        *(u32x4*)d = w0;
+        *(u32x4*)(d + 4) = w1;
+      }
+      __syncthreads();
+      if (WN == 2 || (wm >> 1) == h) {
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
-        a[ks][i] = sb_pair_frag(Vs, RC_LDV, ks * 8 + 4 * (lane >> 5), wm * 64 + 32 * i + (lane & 31));
+        for (int ks = 0; ks < NKS; ++ks)
+#pragma unroll
+          for (int i = 0; i < 2; ++i)
+            a[ks][i] = sb_pair_frag(Vs, RC_LDV, ks * 8 + 4 * (lane >> 5), (wm & 1) * 64 + 32 * i + (lane & 31));
+      }
+    }
     __syncthreads();   // the V staging area is free: it overlaps Cs and the U buffers
     if ((g.k & 15) != 0 && t < 2 * RC_BM) {
       // k = 16 NKS - 8: the last chunk of every row is padding that no copy writes
@@ -796,33 +812,40 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
       const bool has_next = rt + 1 < rt_last;
       // next tile into the other buffer: its last readers (tile it-1) are past a barrier
       if (has_next) issue_copy(rt + 1, cur ^ 1);
-      // Wait for this tile's copies.  Younger than them, and allowed to stay in flight: the 4
+      // Wait for this tile's copies.  Younger than them, and allowed to stay in flight: the NST
       // stores of the previous tile (every tile but the last of the matrix is full, so each
-      // wave issued exactly 4) and the copies just issued (at least NCOPY_MIN per wave).
+      // wave issued exactly NST) and the copies just issued (at least NCOPY_MIN per wave).
       if (has_next) {
-        if (it > 0) SB_WAIT_VMCNT(4 + NCOPY_MIN); else SB_WAIT_VMCNT(NCOPY_MIN);
+        if (it > 0) SB_WAIT_VMCNT(NST + NCOPY_MIN); else SB_WAIT_VMCNT(NCOPY_MIN);
       } else {
-        if (it > 0) SB_WAIT_VMCNT(4); else SB_WAIT_VMCNT(0);
+        if (it > 0) SB_WAIT_VMCNT(NST); else SB_WAIT_VMCNT(0);
       }
       sb_barrier_lds();   // copies of all waves landed; previous tile's reads of Cs are complete
 
       const unsigned char* ub = Ub + cur * UBUF;
-      f32x16 acc[2];
+      f32x16 acc[2][RH];
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[i][r] = 0.0f;
-      const int urow = wn * 32 + (lane & 31);
-      // U fragments are read four K steps ahead of the matrix instructions that use them
-      constexpr int NG = (NKS + 3) / 4;
-      bf16x8 b[2][4];
-      auto read_group = [&](int gi, bf16x8* dst) {
+        for (int j = 0; j < RH; ++j)
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int ks = 4 * gi + u;
+          for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+      const int urow = wn * 32 + (lane & 31);
+      // U fragments are read one group of K steps ahead of the matrix instructions that use them
+      constexpr int GS = WIDE ? 2 : 4;
+      constexpr int NG = (NKS + GS - 1) / GS;
+      bf16x8 b[2][GS][RH];
+      auto read_group = [&](int gi, bf16x8 (*dst)[RH]) {
+#pragma unroll
+        for (int u = 0; u < GS; ++u) {
+          const int ks = GS * gi + u;
           if (ks < NKS) {
             const int c = 2 * ks + (lane >> 5);
-            dst[u] = *(const bf16x8*)(ub + (urow * CPR + (c + urow) % CPR) * 16);
+#pragma unroll
+            for (int j = 0; j < RH; ++j) {
+              const int ur = urow + 32 * j;
+              dst[u][j] = *(const bf16x8*)(ub + (ur * CPR + (c + ur) % CPR) * 16);
+            }
           }
         }
       };
@@ -831,11 +854,14 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
       for (int gi = 0; gi < NG; ++gi) {
         if (gi + 1 < NG) read_group(gi + 1, b[(gi + 1) & 1]);
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int ks = 4 * gi + u;
+        for (int u = 0; u < GS; ++u) {
+          const int ks = GS * gi + u;
           if (ks < NKS && !RC_SKIPPED(4)) {
-            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][0], b[gi & 1][u], acc[0], 0, 0, 0);
-            acc[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][1], b[gi & 1][u], acc[1], 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < RH; ++j) {
+              acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][0], b[gi & 1][u][j], acc[0][j], 0, 0, 0);
+              acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][1], b[gi & 1][u][j], acc[1][j], 0, 0, 0);
+            }
           }
         }
       }
@@ -843,53 +869,60 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
 #pragma unroll
       for (int i = 0; i < 2; ++i)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          bf16x4 o;
+        for (int j = 0; j < RH; ++j)
 #pragma unroll
-          for (int u = 0; u < 4; ++u) o[u] = (bf16_t)acc[i][4 * q + u];
-          const int col = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
-          *(bf16x4*)(Cs + urow * RC_LDC + col) = o;
-        }
+          for (int q = 0; q < 4; ++q) {
+            bf16x4 o;
+#pragma unroll
+            for (int u = 0; u < 4; ++u) o[u] = (bf16_t)acc[i][j][4 * q + u];
+            const int col = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
+            *(bf16x4*)(Cs + (urow + 32 * j) * LDC + col) = o;
+          }
       sb_barrier_lds();
       const int64_t r0 = (int64_t)rt * RC_BM;
-      bf16x8 o[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int e = t + 256 * q;
-        o[q] = *(const bf16x8*)(Cs + (e >> 4) * RC_LDC + (e & 15) * 8);
-      }
+      for (int q0 = 0; q0 < NST; q0 += 4) {
+        bf16x8 o[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) {
-        const int e = t + 256 * q;
-        const int row = e >> 4, ch = e & 15;
-        const int64_t grow = r0 + row, col = col0 + ch * 8;
-        if (grow < g.m && col + 8 <= g.n && !(RC_SKIPPED(2) && it > 0))
-        {
-          if (g.stream_out) __builtin_nontemporal_store(o[q], (bf16x8*)(g.Xhat + grow * g.ldxh + col));
-          else *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = o[q];
+        for (int q = 0; q < 4; ++q) {
+          const int e = t + NT * (q0 + q);
+          o[q] = *(const bf16x8*)(Cs + (e / (BN / 8)) * LDC + (e % (BN / 8)) * 8);
+        }
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int e = t + NT * (q0 + q);
+          const int row = e / (BN / 8), ch = e % (BN / 8);
+          const int64_t grow = r0 + row, col = col0 + ch * 8;
+          if (grow < g.m && col + 8 <= g.n && !(RC_SKIPPED(2) && it > 0)) {
+            if (g.stream_out) __builtin_nontemporal_store(o[q], (bf16x8*)(g.Xhat + grow * g.ldxh + col));
+            else *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = o[q];
+          }
         }
       }
     }
   }
 }
 
+static inline int reconstruct_wn_for(int nks) { return (nks > 8 && nks <= 16) ? 4 : 2; }
 static size_t reconstruct_lds_bytes(int nks) {
-  const size_t run = (size_t)RC_CS_BYTES + (size_t)2 * RC_BM * 2 * nks * 16;
+  const int bn = 64 * reconstruct_wn_for(nks);
+  const size_t run = (size_t)RC_BM * (bn + 8) * 2 + (size_t)2 * RC_BM * 2 * nks * 16;
   const size_t stage = (size_t)nks * 8 * RC_LDV * sizeof(unsigned int);
   return std::max(run, stage);
 }
 
 template <int NKS>
 static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) {
+  constexpr bool WIDE = NKS > 8 && NKS <= 16;    // beyond 16 K steps the V fragments leave no registers
   static bool attr_done = false;
   const size_t lds = reconstruct_lds_bytes(NKS);
   if (lds > 64 * 1024 && !attr_done) {
-    hipError_t e = hipFuncSetAttribute((const void*)reconstruct_mfma_kernel<NKS>,
+    hipError_t e = hipFuncSetAttribute((const void*)reconstruct_mfma_kernel<NKS, WIDE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(reconstruct LDS)");
     attr_done = true;
   }
-  LORACT_LAUNCH("reconstruct", s, reconstruct_mfma_kernel<NKS>, grid, dim3(256), lds, g);
+  LORACT_LAUNCH("reconstruct", s, (reconstruct_mfma_kernel<NKS, WIDE>), grid, dim3(256), lds, g);
   return LORACT_OK;
 }
 
@@ -897,8 +930,9 @@ static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) 
 static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
   const int nks = (g.k + 15) / 16;
   g.stream_out = sb_streams_past_cache(g.m * g.n * 2);
+  g.bn = 64 * reconstruct_wn_for(nks);
   g.row_tiles = (int)ceil_div64(g.m, RC_BM);
-  g.items = ceil_div64(g.n, RC_BN) * g.row_tiles;
+  g.items = ceil_div64(g.n, g.bn) * g.row_tiles;
   // as many workgroups as stay resident: LDS allows 160 KB per CU, registers about 2 per CU
   const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)reconstruct_lds_bytes(nks)));
   const int64_t wgs = std::min<int64_t>(g.items, 256 * per_cu);
