@@ -366,14 +366,28 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
       gdiag_reg[c] = gdiag[jb + c];
       thr[c] = tol * gdiag_reg[c];
     }
+    // the first pass's rows below are fetched together with the diagonal block, before the barrier:
+    // one memory round trip per panel instead of two (they are written only after it)
+    double afirst[OF_NB];
+    {
+      const int row = below + wave * 48 + lane - 16;
+      const bool on = lane >= 16 && row < kp;
+#pragma unroll
+      for (int c = 0; c < OF_NB; ++c) afirst[c] = on ? Am[row * lda + jb + c] : 0.0;
+    }
     __syncthreads();   // every wave has read the unfactored diagonal block
     for (int pass = 0; pass < npass; ++pass) {
     const int row = (lane < 16) ? (jb + lane) : (below + (pass * NWAVES + wave) * 48 + lane - 16);
     const bool row_ok = row < kp;
     double a[OF_NB];
+    if (pass == 0) {
 #pragma unroll
-    for (int c = 0; c < OF_NB; ++c)
-      a[c] = (lane < 16) ? dsave[c] : (row_ok ? Am[row * lda + jb + c] : 0.0);
+      for (int c = 0; c < OF_NB; ++c) a[c] = (lane < 16) ? dsave[c] : afirst[c];
+    } else {
+#pragma unroll
+      for (int c = 0; c < OF_NB; ++c)
+        a[c] = (lane < 16) ? dsave[c] : (row_ok ? Am[row * lda + jb + c] : 0.0);
+    }
 #ifdef OF_TIMING
     { long long now = wall_clock64(); t_pl += now - t_mark; t_m2 = now; }
 #endif
@@ -429,29 +443,46 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
 #endif
 
     // ---- trailing update of the lower triangle: A[I][C] -= P_I P_C^T per 16 x 16 block (C <= I),
-    // one block per wave at a time on the float64 matrix cores, the panel read from Pt.
+    // on the float64 matrix cores, the panel read from Pt.
     {
       const int nb16 = nrows_below / OF_NB;
       const int nblocks = nb16 * (nb16 + 1) / 2;
       const int lc = lane & 15, lr = lane >> 4;
-      for (int e = wave; e < nblocks && !OF_SKIPPED(2); e += CHOL_THREADS / 64) {
-        int ti = (int)((sqrtf(8.0f * (float)e + 1.0f) - 1.0f) * 0.5f);
-        while (ti * (ti + 1) / 2 > e) --ti;
-        while ((ti + 1) * (ti + 2) / 2 <= e) ++ti;
-        const int tc = e - ti * (ti + 1) / 2;
-        double* ablk = Am + (below + OF_NB * ti + lr) * lda + below + OF_NB * tc + lc;
-        f64x4 acc;
-        double pa[4], pb[4];
+      // Several blocks per wave and trip: the loads of all their accumulators are issued before
+      // the first matrix instruction, so that their latency (LDS, or L2 when the matrix lives in
+      // global memory) is paid once per trip.  The panel operands come from LDS at the point of use.
+      constexpr int NWV = CHOL_THREADS / 64, TB = 4;
+      for (int e0 = wave; e0 < nblocks && !OF_SKIPPED(2); e0 += NWV * TB) {
+        double* ablk[TB];
+        int ta[TB], tb[TB];
+        f64x4 acc[TB];
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          acc[r] = ablk[4 * r * lda];
-          pa[r] = -Pt[(4 * r + lr) * ptld + OF_NB * ti + lc];
-          pb[r] = Pt[(4 * r + lr) * ptld + OF_NB * tc + lc];
+        for (int b = 0; b < TB; ++b) {
+          const int e = e0 + b * NWV;
+          const int ee = e < nblocks ? e : e0;            // idle slots redo the first block's loads
+          int ti = (int)((sqrtf(8.0f * (float)ee + 1.0f) - 1.0f) * 0.5f);
+          while (ti * (ti + 1) / 2 > ee) --ti;
+          while ((ti + 1) * (ti + 2) / 2 <= ee) ++ti;
+          const int tc = ee - ti * (ti + 1) / 2;
+          ta[b] = OF_NB * ti + lc;
+          tb[b] = OF_NB * tc + lc;
+          ablk[b] = Am + (below + OF_NB * ti + lr) * lda + below + OF_NB * tc + lc;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) acc[b][r] = ablk[b][4 * r * lda];
         }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) acc = mfma_f64(pa[r], pb[r], acc);
+        for (int b = 0; b < TB; ++b) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) ablk[4 * r * lda] = acc[r];
+          for (int r = 0; r < 4; ++r)
+            acc[b] = mfma_f64(-Pt[(4 * r + lr) * ptld + ta[b]], Pt[(4 * r + lr) * ptld + tb[b]], acc[b]);
+        }
+#pragma unroll
+        for (int b = 0; b < TB; ++b) {
+          if (e0 + b * NWV < nblocks) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) ablk[b][4 * r * lda] = acc[b][r];
+          }
+        }
       }
     }
     __syncthreads();
