@@ -15,10 +15,6 @@
 // ---------------------------------------------------------------------------------------------
 // Small utility kernels.
 
-struct IdxPack {
-  int32_t v[LORACT_MAX_RANK];
-};
-
 // Copies the sampled row ids (passed by value in the kernel arguments, so no host-to-device
 // copy is needed) into the workspace and clears the status word.
 __global__ void store_indices_kernel(IdxPack pack, int count, int32_t* dst, int32_t* status) {
@@ -187,7 +183,13 @@ static T* ws_ptr(const Ctx& c, size_t off) { return (T*)(c.ws + off); }
 
 // Y (m x l) = X * Bt^T where Bt is l x n, K-contiguous rows of length n (optionally gathered
 // from X itself through the sampled row ids).  Algorithm 1, step 2 and the second half of step 5.
-static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows, void* Y) {
+// The matrix-core sketch can take the sampled row ids in its own kernel arguments (`pack`, and
+// then also clears the status word), which saves the launch that stores them in the workspace.
+static bool sketch_takes_ids(const Ctx& c) {
+  return c.pl.bf16_path && sb_aligned(c.X, c.p->ldx) && c.p->n % 64 == 0;
+}
+static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows, void* Y,
+                  const IdxPack* pack = nullptr) {
   const int64_t m = c.p->m, n = c.p->n;
   const int l = c.pl.l;
   if (c.pl.bf16_path) {
@@ -197,6 +199,8 @@ static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows
       a.B = (const bf16_t*)Bt; a.ldb = ldb; a.b_rows = rows; a.l = l; a.kp = c.pl.kp;
       a.Y = (float*)Y; a.part = ws_ptr<float>(c, c.pl.off_fpart); a.splits = c.pl.sketch_splits;
       a.k_per_split = 0; a.run_flag = nullptr;
+      a.ids_in_args = 0; a.clear_status = nullptr;
+      if (pack) { a.ids = *pack; a.ids_in_args = 1; a.clear_status = c.status; }
       return launch_sketch_mfma(c.s, a);
     }
     return launch_gemm_bf16("sketch_generic", c.s, (const bf16_t*)c.X, c.p->ldx, 1, (const bf16_t*)Bt,
@@ -277,6 +281,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   SketchArgs a;                       // C = Q1b T^T  (T symmetric), into the free sketch buffer
   a.X = Q1b; a.ldx = kp; a.m = m; a.n = kp; a.B = nsT; a.ldb = kp; a.b_rows = nullptr; a.l = kp; a.kp = kp;
   a.Y = (float*)Y; a.part = nullptr; a.splits = 1; a.k_per_split = 0; a.run_flag = ns_flag;
+  a.ids_in_args = 0; a.clear_status = nullptr;
   LORACT_TRY(launch_sketch_mfma(c.s, a, "ns_correct"));
   const int blocks = (int)std::min<int64_t>(ceil_div64(m * (kp / 4), 256), 2048);
   LORACT_LAUNCH("ns_finalize", c.s, ns_finalize_kernel, dim3(blocks), dim3(256), 0, (const float*)tmp,
@@ -455,11 +460,15 @@ int loract_compress(const void* X_dev, const loract_params* p, const int32_t* id
     LORACT_TRY(sample_indices_host(p->m, l, p->seed, pack.v));
   }
   int32_t* idx_dev = ws_ptr<int32_t>(c, c.pl.off_idx);
-  LORACT_LAUNCH("store_indices", s, store_indices_kernel, dim3((l + 255) / 256), dim3(256), 0, pack,
-                l, idx_dev, status_dev);
   void* Y = c.ws + c.pl.off_a;
   void* tmp = c.ws + c.pl.off_b;
-  LORACT_TRY(sketch(c, X_dev, p->ldx, idx_dev, Y));       // steps 1-2
+  if (sketch_takes_ids(c)) {
+    LORACT_TRY(sketch(c, X_dev, p->ldx, nullptr, Y, &pack));   // steps 1-2
+  } else {
+    LORACT_LAUNCH("store_indices", s, store_indices_kernel, dim3((l + 255) / 256), dim3(256), 0, pack,
+                  l, idx_dev, status_dev);
+    LORACT_TRY(sketch(c, X_dev, p->ldx, idx_dev, Y));          // steps 1-2
+  }
   LORACT_TRY(power_iterations(c, Y, tmp));                // steps 3-6
   if (l == k) return finish_factors(c, Y, tmp, U_dev, V_dev);   // steps 7-8
   return truncate_factors(c, Y, tmp, U_dev, V_dev);       // l > k sampled rows: rank-k truncation
@@ -547,6 +556,7 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
     a.B = (const bf16_t*)Blora_dev; a.ldb = n_out; a.b_rows = nullptr; a.l = r_lora; a.kp = rp;
     a.Y = (float*)(ws + lp.off_g); a.part = (float*)(ws + lp.off_gpart); a.splits = lp.g_splits;
     a.k_per_split = 0; a.run_flag = nullptr;
+    a.ids_in_args = 0; a.clear_status = nullptr;
     bf16_t* Gsplit = (bf16_t*)(ws + lp.off_gsplit);
     LORACT_TRY(launch_sketch_mfma(s, a, "lora_dyb", Gsplit));
     // [T_hi | T_lo] = U^T [G_hi | G_lo]  (k x 2rp)

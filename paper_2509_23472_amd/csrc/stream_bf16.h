@@ -104,6 +104,11 @@ static int launch_sum_partials(hipStream_t s, const float* part, int splits, int
 // row r stored at position c ^ (r & 7), so that the 16-byte fragment reads of 8 consecutive rows
 // hit 8 different bank groups.  Requires n % 64 == 0 (no partial slab) on this path.
 
+// Row ids passed by value inside kernel arguments (no host-to-device copy needed).
+struct IdxPack {
+  int32_t v[LORACT_MAX_RANK];
+};
+
 struct SketchArgs {
   const bf16_t* X;
   int64_t ldx;
@@ -119,6 +124,9 @@ struct SketchArgs {
   int64_t k_per_split;   // multiple of SB_BK
   const int32_t* run_flag;   // optional: the launch does nothing when *run_flag == 0
   int stream_x;              // set by the launcher: X is too large to stay cached, copy it non-temporally
+  int ids_in_args;           // the gather ids are `ids` below (read from the kernel-argument segment), not b_rows
+  int32_t* clear_status;     // optional: word that the first workgroup sets to zero
+  IdxPack ids;
 };
 
 // WM = 64-row wave groups per workgroup: 2 (4 waves, 128 rows) or 4 (8 waves, 256 rows; halves the
@@ -131,6 +139,13 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   constexpr int LOADS = 4 + NB;         // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
   if (g.run_flag && *g.run_flag == 0) return;
+  if (g.clear_status && threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
+    *g.clear_status = 0;
+  // ids carried in the arguments are read through the kernel-argument segment, which is ordinary
+  // read-only memory and so can be indexed per lane (g is the kernel's only argument, offset 0)
+  const int32_t* const gather =
+      g.ids_in_args ? (const int32_t*)((const char*)__builtin_amdgcn_kernarg_segment_ptr() + offsetof(SketchArgs, ids))
+                    : g.b_rows;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int wm = wave >> 1, wn = wave & 1;
@@ -161,8 +176,8 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   for (int i = 0; i < NB; ++i) {
     const int j = col0 + (wave * NB + i) * 8 + sub;
     int64_t r = 0;
-    if (j < g.l) r = g.b_rows ? (int64_t)g.b_rows[j] : (int64_t)j;
-    else r = g.b_rows ? (int64_t)g.b_rows[0] : 0;
+    if (j < g.l) r = gather ? (int64_t)gather[j] : (int64_t)j;
+    else r = gather ? (int64_t)gather[0] : 0;
     b_src[i] = g.B + r * g.ldb + kbeg + kc * 8;
   }
   auto issue = [&](int slab) {
