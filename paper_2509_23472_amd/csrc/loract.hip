@@ -565,11 +565,8 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
     pa.l = k; pa.V = ws + lp.off_tsplit; pa.out_ek = EK_F32; pa.part = (float*)(ws + lp.off_ppart);
     LORACT_TRY(launch_project_mfma(s, pa, "lora_utg"));
     // dA = scale * V^T (T_hi + T_lo)
-    const int64_t items = n * (rp / 4);
-    LORACT_LAUNCH("lora_vtt", s, lora_vtt_kernel, dim3((unsigned)ceil_div64(items, 256)), dim3(256),
-                  (size_t)k * rp * sizeof(float), (const bf16_t*)V_dev,
-                  (const float*)(ws + lp.off_tsplit), (int)k, n, (int)r_lora, rp, scale, dA_dev);
-    return LORACT_OK;
+    return launch_lora_vtt(s, (const bf16_t*)V_dev, (const float*)(ws + lp.off_tsplit), (int)k, n,
+                           (int)r_lora, rp, scale, dA_dev);
   }
   // G = dY B_lora^T  (m x r): the only pass over the large operand
   if (grad_dtype == LORACT_BF16)

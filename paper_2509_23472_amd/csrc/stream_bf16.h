@@ -965,33 +965,83 @@ static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
 // ---------------------------------------------------------------------------------------------
 // Last contraction of the LoRA gradient: dA (n x r) = scale * V^T (T_hi + T_lo), with V (k x n,
 // bf16) and the k x 2rp fp32 matrix [T_hi | T_lo] produced by the split-bf16 projection.
-// One thread per (column of V, group of 4 output columns); T is staged in LDS.
+// A workgroup owns 32 columns of V; its 256 threads are 32 columns x 8 groups of the contraction
+// index, so that each thread's chain of loads is k / 8 long; the 8 partial sums of an output are
+// added in a fixed order through LDS.  RP = 16 RP16 is the padded LoRA rank.
 
+template <int RP16>
 __global__ __launch_bounds__(256) void lora_vtt_kernel(const bf16_t* V, const float* Tsplit,
-                                                       int k, int64_t n, int r, int rp,
-                                                       float scale, float* dA) {
-  extern __shared__ float lv_T[];   // [k][rp]
-  for (int e = threadIdx.x; e < k * rp; e += 256) {
-    const int q = e / rp, c = e - q * rp;
-    lv_T[e] = Tsplit[(int64_t)q * 2 * rp + c] + Tsplit[(int64_t)q * 2 * rp + rp + c];
+                                                       int k, int64_t n, int r, float scale,
+                                                       float* dA) {
+  constexpr int RP = 16 * RP16;
+  extern __shared__ float lv_T[];   // T [k][RP], then partial sums [8][32][RP + 1]
+  float* const red = lv_T + k * RP;
+  for (int e = threadIdx.x; e < k * RP; e += 256) {
+    const int q = e / RP, c = e - q * RP;
+    lv_T[e] = Tsplit[(int64_t)q * 2 * RP + c] + Tsplit[(int64_t)q * 2 * RP + RP + c];
   }
   __syncthreads();
-  const int groups = rp >> 2;
-  const int64_t item = (int64_t)blockIdx.x * 256 + threadIdx.x;
-  const int64_t j = item % n;                 // consecutive threads -> consecutive columns of V
-  const int cg = (int)(item / n);
-  if (cg >= groups) return;
-  f32x4 acc = {0.0f, 0.0f, 0.0f, 0.0f};
-  int q = 0;
-  for (; q + 8 <= k; q += 8) {            // 8 independent loads in flight
+  const int cj = threadIdx.x & 31, kg = threadIdx.x >> 5;
+  const int64_t j = (int64_t)blockIdx.x * 32 + cj;
+  const int64_t jc = j < n ? j : n - 1;        // columns past the end repeat the last one, never stored
+  const int per = (k + 7) >> 3;
+  const int q_begin = kg * per, q_end = (q_begin + per < k) ? q_begin + per : k;
+  f32x4 acc[RP / 4];
+#pragma unroll
+  for (int c = 0; c < RP / 4; ++c) acc[c] = (f32x4){0.0f, 0.0f, 0.0f, 0.0f};
+  int q = q_begin;
+  for (; q + 8 <= q_end; q += 8) {            // 8 independent loads in flight
     float v[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) v[u] = (float)V[(int64_t)(q + u) * n + j];
+    for (int u = 0; u < 8; ++u) v[u] = (float)V[(int64_t)(q + u) * n + jc];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) acc += v[u] * *(const f32x4*)(lv_T + (q + u) * rp + 4 * cg);
+    for (int u = 0; u < 8; ++u)
+#pragma unroll
+      for (int c = 0; c < RP / 4; ++c) acc[c] += v[u] * *(const f32x4*)(lv_T + (q + u) * RP + 4 * c);
   }
-  for (; q < k; ++q) acc += (float)V[(int64_t)q * n + j] * *(const f32x4*)(lv_T + q * rp + 4 * cg);
+  for (; q < q_end; ++q) {
+    const float v = (float)V[(int64_t)q * n + jc];
 #pragma unroll
-  for (int u = 0; u < 4; ++u)
-    if (4 * cg + u < r) dA[j * r + 4 * cg + u] = scale * acc[u];
+    for (int c = 0; c < RP / 4; ++c) acc[c] += v * *(const f32x4*)(lv_T + q * RP + 4 * c);
+  }
+#pragma unroll
+  for (int c = 0; c < RP / 4; ++c)
+#pragma unroll
+    for (int u = 0; u < 4; ++u) red[(kg * 32 + cj) * (RP + 1) + 4 * c + u] = acc[c][u];
+  __syncthreads();
+  for (int o = threadIdx.x; o < 32 * RP; o += 256) {
+    const int col = o / RP, c = o - col * RP;
+    float sum = 0.0f;
+#pragma unroll
+    for (int g8 = 0; g8 < 8; ++g8) sum += red[(g8 * 32 + col) * (RP + 1) + c];
+    const int64_t jo = (int64_t)blockIdx.x * 32 + col;
+    if (jo < n && c < r) dA[jo * r + c] = scale * sum;
+  }
+}
+
+template <int RP16>
+static int launch_lora_vtt_rp(hipStream_t s, const bf16_t* V, const float* Tsplit, int k, int64_t n, int r,
+                              float scale, float* dA) {
+  const int rp = 16 * RP16;
+  const size_t lds = ((size_t)k * rp + (size_t)8 * 32 * (rp + 1)) * sizeof(float);
+  static size_t attr_bytes = 64 * 1024;
+  if (lds > attr_bytes) {
+    hipError_t e = hipFuncSetAttribute((const void*)lora_vtt_kernel<RP16>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(lora_vtt LDS)");
+    attr_bytes = lds;
+  }
+  LORACT_LAUNCH("lora_vtt", s, lora_vtt_kernel<RP16>, dim3((unsigned)ceil_div64(n, 32)), dim3(256), lds, V,
+                Tsplit, k, n, r, scale, dA);
+  return LORACT_OK;
+}
+static int launch_lora_vtt(hipStream_t s, const bf16_t* V, const float* Tsplit, int k, int64_t n, int r,
+                           int rp, float scale, float* dA) {
+  switch (rp / 16) {
+    case 1: return launch_lora_vtt_rp<1>(s, V, Tsplit, k, n, r, scale, dA);
+    case 2: return launch_lora_vtt_rp<2>(s, V, Tsplit, k, n, r, scale, dA);
+    case 3: return launch_lora_vtt_rp<3>(s, V, Tsplit, k, n, r, scale, dA);
+    case 4: return launch_lora_vtt_rp<4>(s, V, Tsplit, k, n, r, scale, dA);
+    default: return LORACT_ERR_UNSUPPORTED;
+  }
 }
