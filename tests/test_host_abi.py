@@ -95,3 +95,48 @@ def test_compress_rejects_bad_arguments_before_touching_the_device():
     assert lib.loract_lora_grad_workspace_bytes(8, 8, 2, 8, 65, ctypes.byref(sz)) == -1
     assert lib.loract_lora_grad_workspace_bytes(8192, 4096, 128, 4096, 16, ctypes.byref(sz)) == 0
     assert sz.value > 0
+
+
+def _python_sources(*roots):
+    import os
+    here = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    for root in roots:
+        path = os.path.join(here, root)
+        if os.path.isfile(path):
+            yield path
+            continue
+        for dirpath, _, files in os.walk(path):
+            for f in files:
+                if f.endswith((".py", ".h", ".hip")):
+                    yield os.path.join(dirpath, f)
+
+
+def test_product_path_is_independent_of_the_oracle_and_of_working_files():
+    # The oracle is test infrastructure: nothing in the package may import it (the smoke check and
+    # the benchmark's cpu_baseline leg are the only callers outside tests/), and nothing committed
+    # may reach into the scratch folder or the reference text.
+    import re
+    for path in _python_sources("paper_2509_23472_amd", "workloads"):
+        text = open(path, encoding="utf-8").read()
+        assert not re.search(r"^\s*(from|import)\s+oracle\b", text, re.M), path
+    for path in _python_sources("paper_2509_23472_amd", "workloads", "oracle", "bench.py",
+                                "__graft_entry__.py", "tests"):
+        if path.endswith("test_host_abi.py"):
+            continue
+        text = open(path, encoding="utf-8").read()
+        assert "/root/reference" not in text, path
+        assert not re.search(r"[\"'/]_work/", text), path
+    oracle_text = "".join(open(p, encoding="utf-8").read() for p in _python_sources("oracle"))
+    assert "paper_2509_23472_amd" not in oracle_text.replace("must never be imported by the product package", "")
+
+
+def test_missing_library_fails_loudly(monkeypatch, tmp_path):
+    # no CPU or eager fallback: without the built shared object the loader raises
+    monkeypatch.setattr(_lib, "_lib", None)
+    monkeypatch.setattr(_lib, "LIB_PATH", str(tmp_path / "libloract_missing.so"), raising=False)
+    try:
+        with pytest.raises(Exception):
+            _lib.load()
+    finally:
+        monkeypatch.undo()
+        _lib.load()
