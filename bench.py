@@ -26,6 +26,7 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0            # MI355X published HBM3E bandwidth
 FP64_VECTOR_PEAK_TFLOPS = 78.6   # MI355X published fp64 vector rate
+BF16_MFMA_PEAK_TFLOPS = 2500.0   # MI355X published dense bf16 matrix rate
 
 
 def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: int, launches: float):
@@ -289,6 +290,13 @@ def main() -> int:
     total_ms = sum(ms for ms, _ in prof.values())
     for name, (ms, cnt) in prof.items():
         kernels[name]["share"] = round(ms / total_ms, 3)
+    # matrix-core utilisation of the three dense contractions (2 m n k flops each) against the
+    # published dense bf16 peak
+    for name in ("sketch", "project", "reconstruct"):
+        if name in kernels:
+            tf = 2.0 * m * n * k / (kernels[name]["avg_us"] * 1e-6) / 1e12
+            kernels[name]["mfma_tflops"] = round(tf, 1)
+            kernels[name]["mfma_frac"] = round(tf / BF16_MFMA_PEAK_TFLOPS, 4)
     dom = max(prof.items(), key=lambda kv: kv[1][0])[0]
     d_bound, d_amount, d_unit = algorithmic_cost(dom, m, n, k, b, n_out, r_l, prof[dom][1] / args.steps)
     d_avg_s = prof[dom][0] * 1e-3 / prof[dom][1]

@@ -136,7 +136,7 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_q1b = take(pl->bf16_path ? (size_t)m * pl->kp * 2 : 0);
   pl->off_nsT = take(pl->bf16_path ? (size_t)pl->kp * pl->kp * 2 : 0);
   pl->off_gbak = take(pl->bf16_path && pl->kp > 128 ? (size_t)pl->kp * pl->kp * 8 : 0);
-  pl->off_flag = take(64 + 8 * 16 * 16);   // flag word, then up to 16 x 15 shares of ||E||^2
+  pl->off_flag = take(64 + 8 * 64 * 16);   // flag word, then up to 64 x 15 shares of ||E||^2
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
@@ -272,7 +272,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr,
                               ns_ok ? ns_e2 : nullptr));
   ch.round = 2;
-  if (ns_ok) { ch.ns_e2 = ns_e2; ch.ns_e2_count = 16 * gram_nblocks(kp); ch.ns_flag = ns_flag; ch.ns_tol = 0.015; }
+  if (ns_ok) { ch.ns_e2 = ns_e2; ch.ns_e2_count = 64 * gram_nblocks(kp); ch.ns_flag = ns_flag; ch.ns_tol = 0.015; }
   LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = tmp; t.Q = Q; t.ldq = l; t.out_ek = q_ek; t.out_cols = l; t.Qb = Qb; t.ldqb = l;
   t.skip_flag = ns_ok ? ns_flag : nullptr;

@@ -153,31 +153,38 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, in
   const int b = blockIdx.y;
   int bi, bj;
   gram_block_of(b, &bi, &bj);
-  const int e = blockIdx.x * 256 + threadIdx.x;     // gridDim.x = 16
+  // four lanes per element: lane `sub` adds the chunks sub, sub + 4, ... in ascending order and the
+  // four sums are combined as (s0 + s1) + (s2 + s3), a fixed order whatever the chunk count
+  const int sub = threadIdx.x & 3;
+  const int e = blockIdx.x * 64 + (threadIdx.x >> 2);     // gridDim.x = 64
   const int i = bi * 64 + (e >> 6), j = bj * 64 + (e & 63);
   double contrib = 0.0;
   if (i < kp && j < kp) {
     const double* src = part + (int64_t)b * 4096 + e;
     const int64_t stride = (int64_t)nblocks * 4096;
     double s = 0.0;
-    int c = 0;
-    for (; c + 8 <= chunks; c += 8) {
+    int c = sub;
+    for (; c + 28 < chunks; c += 32) {
       double v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(c + u) * stride];
+      for (int u = 0; u < 8; ++u) v[u] = src[(int64_t)(c + 4 * u) * stride];
 #pragma unroll
       for (int u = 0; u < 8; ++u) s += v[u];
     }
-    for (; c < chunks; ++c) s += src[(int64_t)c * stride];
-    G[(int64_t)i * kp + j] = s;
-    if (G_copy) G_copy[(int64_t)i * kp + j] = s;
-    if (ns_T) {
-      double ev = 0.0;
-      if (i < k && j < k) ev = s - (i == j ? 1.0 : 0.0);
-      const bf16_t tv = (bf16_t)(float)(-0.5 * ev);
-      ns_T[(int64_t)i * kp + j] = tv;
-      if (bi != bj) ns_T[(int64_t)j * kp + i] = tv;
-      contrib = (bi == bj) ? ev * ev : 2.0 * ev * ev;
+    for (; c < chunks; c += 4) s += src[(int64_t)c * stride];
+    s += __shfl_xor(s, 1);
+    s += __shfl_xor(s, 2);
+    if (sub == 0) {
+      G[(int64_t)i * kp + j] = s;
+      if (G_copy) G_copy[(int64_t)i * kp + j] = s;
+      if (ns_T) {
+        double ev = 0.0;
+        if (i < k && j < k) ev = s - (i == j ? 1.0 : 0.0);
+        const bf16_t tv = (bf16_t)(float)(-0.5 * ev);
+        ns_T[(int64_t)i * kp + j] = tv;
+        if (bi != bj) ns_T[(int64_t)j * kp + i] = tv;
+        contrib = (bi == bj) ? ev * ev : 2.0 * ev * ev;
+      }
     }
   }
   if (ns_T) {
@@ -286,8 +293,17 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   // ---- round 2: is Q1 already orthonormal enough for a Newton-Schulz finish?  gram_reduce_kernel
   // has left ||E||_F^2 in pieces (and T = -E/2); on this branch the kernel ends here.
   if (g.round == 2 && g.ns_flag) {
-    double tot = 0.0;
-    for (int w = 0; w < g.ns_e2_count; ++w) tot += g.ns_e2[w];     // same order in every thread
+    // wave 0 adds the shares (lane i takes shares i, i + 64, ...; butterfly sum, so every lane
+    // ends with the same value) and hands the total to the other waves through LDS
+    if (wave == 0) {
+      double part_sum = 0.0;
+      for (int w = lane; w < g.ns_e2_count; w += 64) part_sum += g.ns_e2[w];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
+      if (lane == 0) misc[1] = part_sum;
+    }
+    __syncthreads();
+    const double tot = misc[1];
     if (tot <= g.ns_tol * g.ns_tol) {       // also false for NaN
       if (t == 0) *g.ns_flag = 1;
       return;
@@ -766,7 +782,7 @@ static size_t gram_partial_bytes(int64_t m, int kp) {
   return (size_t)ceil_div64(m, rows) * nblocks * 4096 * sizeof(double);
 }
 
-// ns_e2 needs 16 * gram_nblocks(kp) doubles.
+// ns_e2 needs 64 * gram_nblocks(kp) doubles.
 static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t m, int kp, int k,
                             double* part, double* G, double* G_copy = nullptr,
                             bf16_t* ns_T = nullptr, double* ns_e2 = nullptr) {
@@ -778,7 +794,7 @@ static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t 
   g.part = part;
   const int chunks = (int)ceil_div64(m, g.rows_per_chunk);
   LORACT_LAUNCH("gram", s, gram_mfma_kernel, dim3(chunks, nblocks), dim3(256), 0, g);
-  LORACT_LAUNCH("gram_reduce", s, gram_reduce_kernel, dim3(16, nblocks), dim3(256), 0,
+  LORACT_LAUNCH("gram_reduce", s, gram_reduce_kernel, dim3(64, nblocks), dim3(256), 0,
                 (const double*)part, chunks, nblocks, kp, k, G, G_copy, ns_T, ns_e2);
   return LORACT_OK;
 }

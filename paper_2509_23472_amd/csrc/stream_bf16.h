@@ -395,6 +395,7 @@ struct ProjectArgs {
   int stream_x;            // X is too large to stay cached: copy it non-temporally
 };
 
+#define PJ_MAX_PARTS 40   // partial tiles per output tile: the launcher keeps it at 32 + 2 boundary shares
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -576,6 +577,15 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
   int64_t w_hi = w_lo;                               // exclusive
   while (w_hi < g.wgs && g.items * w_hi / g.wgs < hi_item) ++w_hi;
   const int64_t tile_floats = (int64_t)g.bmq * g.bnx;
+  // offsets of the tile's partial tiles, worked out once per block (64-bit divisions)
+  __shared__ int64_t slot_off[PJ_MAX_PARTS];
+  const int nparts = (int)(w_hi - w_lo);               // <= PJ_MAX_PARTS by the launcher's cap
+  for (int i = threadIdx.x; i < nparts; i += 256) {
+    const int64_t w = w_lo + i;
+    const int64_t first_tile = (g.items * w / g.wgs) / g.slabs;
+    slot_off[i] = (w * g.segs_max + (tile - first_tile)) * tile_floats;
+  }
+  __syncthreads();
   const int qb = (int)(tile / g.col_blocks), cb = (int)(tile - (int64_t)qb * g.col_blocks);
   const int bnx4 = g.bnx >> 2;
   const int groups = g.bmq * bnx4;
@@ -583,21 +593,17 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
     const int qw = e / bnx4, cw = (e - qw * bnx4) << 2;
     const int64_t q = (int64_t)qb * g.bmq + qw, col = (int64_t)cb * g.bnx + cw;
     if (q >= g.l || col >= g.n) continue;
+    const float* base = g.part + (int64_t)qw * g.bnx + cw;
     f32x4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int64_t w = w_lo; w < w_hi; w += 8) {
+    for (int i = 0; i < nparts; i += 8) {
       // eight partial tiles at a time: loads first (an unused slot re-reads a valid one), then the
       // additions in workgroup order
       f32x4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) {
-        const int64_t wu = (w + u < w_hi) ? w + u : w;
-        const int64_t first_tile = (g.items * wu / g.wgs) / g.slabs;
-        v[u] = *(const f32x4*)(g.part + (wu * g.segs_max + (tile - first_tile)) * tile_floats +
-                               (int64_t)qw * g.bnx + cw);
-      }
+      for (int u = 0; u < 8; ++u) v[u] = *(const f32x4*)(base + slot_off[(i + u < nparts) ? i + u : i]);
 #pragma unroll
       for (int u = 0; u < 8; ++u)
-        if (w + u < w_hi) s4 += v[u];
+        if (i + u < nparts) s4 += v[u];
     }
     if (g.out_ek == EK_F32) {
       *(f32x4*)((float*)g.V + q * g.n + col) = s4;
@@ -637,7 +643,13 @@ static void project_plan(ProjectArgs* g) {
   const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)project_lds_bytes(ntq, ntx, stages, wn)));
   // at least 4 slabs per workgroup: a partial tile costs as much as a slab to write and sum
   int64_t wgs = std::min<int64_t>(256 * per_cu, ceil_div64(g->items, 4));
+  // and at most 32 partial tiles per output tile: the sum walks them one after the other
+  wgs = std::min<int64_t>(wgs, 32 * tiles);
   wgs = std::max<int64_t>(1, std::min<int64_t>(wgs, g->items));
+  // hard bound the sum kernel relies on: shares of floor(items / wgs) slabs or more put at most
+  // ceil(slabs / share) + 1 partial tiles on an output tile
+  while (wgs > 1 && ceil_div64(g->slabs, std::max<int64_t>(1, g->items / wgs)) + 1 > PJ_MAX_PARTS)
+    wgs = wgs * 3 / 4;
   g->wgs = (int)wgs;
   // a share of ceil(items / wgs) consecutive items touches at most this many output tiles
   g->segs_max = (int)(ceil_div64(ceil_div64(g->items, wgs), g->slabs) + 1);
