@@ -589,22 +589,31 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
   const int qb = (int)(tile / g.col_blocks), cb = (int)(tile - (int64_t)qb * g.col_blocks);
   const int bnx4 = g.bnx >> 2;
   const int groups = g.bmq * bnx4;
-  for (int e = blockIdx.x * 256 + threadIdx.x; e < groups; e += gridDim.x * 256) {
-    const int qw = e / bnx4, cw = (e - qw * bnx4) << 2;
+  // four lanes per group of 4 columns: lane `sub` adds the partial tiles sub, sub + 4, ... in
+  // ascending order and the four sums are combined as (s0 + s1) + (s2 + s3), a fixed order
+  const int sub = threadIdx.x & 3;
+  for (int e0 = blockIdx.x * 64; e0 < groups; e0 += gridDim.x * 64) {
+    const int e = e0 + (threadIdx.x >> 2);
+    const int ec = e < groups ? e : groups - 1;          // idle lanes redo the last group, never store
+    const int qw = ec / bnx4, cw = (ec - qw * bnx4) << 2;
     const int64_t q = (int64_t)qb * g.bmq + qw, col = (int64_t)cb * g.bnx + cw;
-    if (q >= g.l || col >= g.n) continue;
     const float* base = g.part + (int64_t)qw * g.bnx + cw;
     f32x4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int i = 0; i < nparts; i += 8) {
-      // eight partial tiles at a time: loads first (an unused slot re-reads a valid one), then the
-      // additions in workgroup order
+    for (int i = sub; i < nparts; i += 32) {
+      // up to eight partial tiles at a time: loads first (an unused slot re-reads a valid one)
       f32x4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = *(const f32x4*)(base + slot_off[(i + u < nparts) ? i + u : i]);
+      for (int u = 0; u < 8; ++u) v[u] = *(const f32x4*)(base + slot_off[(i + 4 * u < nparts) ? i + 4 * u : i]);
 #pragma unroll
       for (int u = 0; u < 8; ++u)
-        if (i + u < nparts) s4 += v[u];
+        if (i + 4 * u < nparts) s4 += v[u];
     }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      s4[u] += __shfl_xor(s4[u], 1);
+      s4[u] += __shfl_xor(s4[u], 2);
+    }
+    if (sub != 0 || e >= groups || q >= g.l || col >= g.n) continue;
     if (g.out_ek == EK_F32) {
       *(f32x4*)((float*)g.V + q * g.n + col) = s4;
     } else {
@@ -685,7 +694,7 @@ static int launch_project_sum(hipStream_t s, const ProjectArgs& g) {
   const int64_t tiles = (int64_t)g.col_blocks * ceil_div64(g.l, g.bmq);
   const int groups = g.bmq * (g.bnx >> 2);
   // enough blocks per tile to occupy the machine, each thread at least one group
-  int bx = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(groups, 256), ceil_div64(2048, tiles)));
+  int bx = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(groups, 64), ceil_div64(4096, tiles)));
   LORACT_LAUNCH("project_sum", s, project_sum_kernel, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, g);
   return LORACT_OK;
 }
