@@ -257,7 +257,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   ch.G = G; ch.G_backup = Gbak; ch.Dinv = Dinv; ch.k = l; ch.kp = kp; ch.tol = 0.0; ch.status = c.status;
   ch.shift_rel = 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16;
   ch.unshifted_thresh = chol_unshifted_thresh(l);
-  ch.ns_e2 = nullptr; ch.ns_e2_count = 0; ch.ns_flag = nullptr; ch.ns_tol = 0.0;
+  ch.ns_e2 = nullptr; ch.ns_e2_count = 0; ch.ns_flag = nullptr; ch.ns_tol = 0.0; ch.ns_exact_tol = 0.0;
   TrsmArgs t;
   t.L = G; t.Dinv = Dinv; t.m = m; t.kp = kp; t.k = l;
   // round 1: Q1 = Y R^{-1} (fp32, plus a bf16 copy for a possible Newton-Schulz finish)
@@ -269,20 +269,22 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   LORACT_TRY(launch_trsm_apply(c.s, t));
   // round 2: either Q = Q1 (I - E/2) when E = Q1^T Q1 - I is small, or a second Cholesky QR
   double* ns_e2 = ws_ptr<double>(c, c.pl.off_flag) + 8;      // after the flag word
-  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr,
-                              ns_ok ? ns_e2 : nullptr));
+  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr, ns_e2));
   ch.round = 2;
-  if (ns_ok) { ch.ns_e2 = ns_e2; ch.ns_e2_count = 64 * gram_nblocks(kp); ch.ns_flag = ns_flag; ch.ns_tol = 0.015; }
+  ch.ns_e2 = ns_e2; ch.ns_e2_count = 64 * gram_nblocks(kp); ch.ns_flag = ns_flag;
+  ch.ns_tol = ns_ok ? 0.015 : 0.0;
+  ch.ns_exact_tol = 1e-6;             // Q1 is then orthonormal to 1e-6 already: nothing for round 2 to do
   LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = tmp; t.Q = Q; t.ldq = l; t.out_ek = q_ek; t.out_cols = l; t.Qb = Qb; t.ldqb = l;
-  t.skip_flag = ns_ok ? ns_flag : nullptr;
+  t.skip_flag = ns_flag;
   LORACT_TRY(launch_trsm_apply(c.s, t));
-  if (!ns_ok) return LORACT_OK;
-  SketchArgs a;                       // C = Q1b T^T  (T symmetric), into the free sketch buffer
-  a.X = Q1b; a.ldx = kp; a.m = m; a.n = kp; a.B = nsT; a.ldb = kp; a.b_rows = nullptr; a.l = kp; a.kp = kp;
-  a.Y = (float*)Y; a.part = nullptr; a.splits = 1; a.k_per_split = 0; a.run_flag = ns_flag;
-  a.ids_in_args = 0; a.clear_status = nullptr;
-  LORACT_TRY(launch_sketch_mfma(c.s, a, "ns_correct"));
+  if (ns_ok) {
+    SketchArgs a;                     // C = Q1b T^T  (T symmetric), into the free sketch buffer
+    a.X = Q1b; a.ldx = kp; a.m = m; a.n = kp; a.B = nsT; a.ldb = kp; a.b_rows = nullptr; a.l = kp; a.kp = kp;
+    a.Y = (float*)Y; a.part = nullptr; a.splits = 1; a.k_per_split = 0; a.run_flag = ns_flag;
+    a.ids_in_args = 0; a.clear_status = nullptr;
+    LORACT_TRY(launch_sketch_mfma(c.s, a, "ns_correct"));
+  }
   const int blocks = (int)std::min<int64_t>(ceil_div64(m * (kp / 4), 256), 2048);
   LORACT_LAUNCH("ns_finalize", c.s, ns_finalize_kernel, dim3(blocks), dim3(256), 0, (const float*)tmp,
                 (const float*)Y, m, kp, l, Q, q_ek, Qb, (const int32_t*)ns_flag);

@@ -177,17 +177,19 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, in
     if (sub == 0) {
       G[(int64_t)i * kp + j] = s;
       if (G_copy) G_copy[(int64_t)i * kp + j] = s;
-      if (ns_T) {
+      if (ns_e2) {
         double ev = 0.0;
         if (i < k && j < k) ev = s - (i == j ? 1.0 : 0.0);
-        const bf16_t tv = (bf16_t)(float)(-0.5 * ev);
-        ns_T[(int64_t)i * kp + j] = tv;
-        if (bi != bj) ns_T[(int64_t)j * kp + i] = tv;
+        if (ns_T) {
+          const bf16_t tv = (bf16_t)(float)(-0.5 * ev);
+          ns_T[(int64_t)i * kp + j] = tv;
+          if (bi != bj) ns_T[(int64_t)j * kp + i] = tv;
+        }
         contrib = (bi == bj) ? ev * ev : 2.0 * ev * ev;
       }
     }
   }
-  if (ns_T) {
+  if (ns_e2) {
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) contrib += __shfl_xor(contrib, off);
     if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = contrib;
@@ -245,7 +247,8 @@ __device__ inline double rsqrt_f64(double x) {
 // round == 2 (Gram matrix of Q1): if ns_flag is given, E = G - I is measured first.  When
 //   ||E||_F <= ns_tol the factorisation is skipped (T = -E/2 was already written by
 //   gram_reduce_kernel) and *ns_flag = 1, so that the caller finishes with the first-order Newton-Schulz correction
-//   Q = Q1 (I - E/2), whose defect is ~ (3/4) ||E||^2.  Otherwise *ns_flag = 0 and the matrix is
+//   Q = Q1 (I - E/2), whose defect is ~ (3/4) ||E||^2.  When ||E||_F <= ns_exact_tol, Q1 is taken as
+//   it is (*ns_flag = 2: no second round at all).  Otherwise *ns_flag = 0 and the matrix is
 //   factored unshifted with the clamping rule of chol.h.
 struct CholArgs {
   double* G;
@@ -260,7 +263,8 @@ struct CholArgs {
   const double* ns_e2;      // round 2: shares of ||E||_F^2 from gram_reduce_kernel
   int ns_e2_count;
   int32_t* ns_flag;
-  double ns_tol;
+  double ns_tol;            // Newton-Schulz finish up to this ||E||_F (0 = not available)
+  double ns_exact_tol;      // Q1 accepted unchanged up to this ||E||_F
 };
 
 template <bool LDS_MODE>
@@ -304,7 +308,11 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
     }
     __syncthreads();
     const double tot = misc[1];
-    if (tot <= g.ns_tol * g.ns_tol) {       // also false for NaN
+    if (tot <= g.ns_exact_tol * g.ns_exact_tol) {     // Q1 is orthonormal as it stands
+      if (t == 0) *g.ns_flag = 2;
+      return;
+    }
+    if (g.ns_tol > 0.0 && tot <= g.ns_tol * g.ns_tol) {       // comparisons are false for NaN
       if (t == 0) *g.ns_flag = 1;
       return;
     }
@@ -724,16 +732,17 @@ __global__ __launch_bounds__(256) void ns_finalize_kernel(const float* Q1, const
                                                           int64_t m, int kp, int l, void* Q,
                                                           int q_ek, bf16_t* Qb,
                                                           const int32_t* flag) {
-  if (*flag == 0) return;
+  const int mode = *flag;            // 0: the second factorisation ran; 1: Q = Q1 + C; 2: Q = Q1
+  if (mode == 0) return;
+  const bool add_c = mode == 1;
   const int c4 = kp >> 2;
   const int64_t total = m * c4;
   const bool vec_ok = (l & 3) == 0 && ((uintptr_t)Q & 15) == 0 && ((uintptr_t)Qb & 7) == 0;
   for (int64_t e = (int64_t)blockIdx.x * 256 + threadIdx.x; e < total; e += (int64_t)gridDim.x * 256) {
     const int64_t r = e / c4;
     const int c = (int)(e - r * c4) << 2;
-    const f32x4 a = *(const f32x4*)(Q1 + r * kp + c);
-    const f32x4 b = *(const f32x4*)(C + r * kp + c);
-    const f32x4 q = a + b;
+    f32x4 q = *(const f32x4*)(Q1 + r * kp + c);
+    if (add_c) q += *(const f32x4*)(C + r * kp + c);
     if (vec_ok) {
       // the row pitch l and the base addresses keep groups of four aligned: vector stores
       if (c < l) {

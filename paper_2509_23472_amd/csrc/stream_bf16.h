@@ -122,7 +122,7 @@ struct SketchArgs {
   float* part;           // [splits][m][kp], used when splits > 1
   int splits;
   int64_t k_per_split;   // multiple of SB_BK
-  const int32_t* run_flag;   // optional: the launch does nothing when *run_flag == 0
+  const int32_t* run_flag;   // optional: the launch does nothing unless *run_flag == 1
   int stream_x;              // set by the launcher: X is too large to stay cached, copy it non-temporally
   int ids_in_args;           // the gather ids are `ids` below (read from the kernel-argument segment), not b_rows
   int32_t* clear_status;     // optional: word that the first workgroup sets to zero
@@ -138,7 +138,7 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int LOADS = 4 + NB;         // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
-  if (g.run_flag && *g.run_flag == 0) return;
+  if (g.run_flag && *g.run_flag != 1) return;
   if (g.clear_status && threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
     *g.clear_status = 0;
   // ids carried in the arguments are read through the kernel-argument segment, which is ordinary
