@@ -568,6 +568,7 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
 
 // V tile blockIdx.y = sum of the partial tiles that cover it, in workgroup order; a thread owns
 // groups of 4 consecutive columns.  The workgroup range of the tile is uniform per block.
+template <int LPG>   // lanes per output group: 4 when an output tile has many partial tiles, else 1
 __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
   const int64_t tile = blockIdx.y;
   const int64_t lo_item = tile * g.slabs, hi_item = lo_item + g.slabs;
@@ -589,29 +590,33 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
   const int qb = (int)(tile / g.col_blocks), cb = (int)(tile - (int64_t)qb * g.col_blocks);
   const int bnx4 = g.bnx >> 2;
   const int groups = g.bmq * bnx4;
-  // four lanes per group of 4 columns: lane `sub` adds the partial tiles sub, sub + 4, ... in
-  // ascending order and the four sums are combined as (s0 + s1) + (s2 + s3), a fixed order
-  const int sub = threadIdx.x & 3;
-  for (int e0 = blockIdx.x * 64; e0 < groups; e0 += gridDim.x * 64) {
-    const int e = e0 + (threadIdx.x >> 2);
+  // LPG = 4 lanes per group of 4 columns: lane `sub` adds the partial tiles sub, sub + 4, ... in
+  // ascending order and the four sums are combined as (s0 + s1) + (s2 + s3), a fixed order;
+  // LPG = 1: one lane adds them all in ascending order
+  constexpr int GPB = 256 / LPG;                         // groups per block and trip
+  const int sub = threadIdx.x % LPG;
+  for (int e0 = blockIdx.x * GPB; e0 < groups; e0 += gridDim.x * GPB) {
+    const int e = e0 + threadIdx.x / LPG;
     const int ec = e < groups ? e : groups - 1;          // idle lanes redo the last group, never store
     const int qw = ec / bnx4, cw = (ec - qw * bnx4) << 2;
     const int64_t q = (int64_t)qb * g.bmq + qw, col = (int64_t)cb * g.bnx + cw;
     const float* base = g.part + (int64_t)qw * g.bnx + cw;
     f32x4 s4 = {0.0f, 0.0f, 0.0f, 0.0f};
-    for (int i = sub; i < nparts; i += 32) {
+    for (int i = sub; i < nparts; i += 8 * LPG) {
       // up to eight partial tiles at a time: loads first (an unused slot re-reads a valid one)
       f32x4 v[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) v[u] = *(const f32x4*)(base + slot_off[(i + 4 * u < nparts) ? i + 4 * u : i]);
+      for (int u = 0; u < 8; ++u) v[u] = *(const f32x4*)(base + slot_off[(i + LPG * u < nparts) ? i + LPG * u : i]);
 #pragma unroll
       for (int u = 0; u < 8; ++u)
-        if (i + 4 * u < nparts) s4 += v[u];
+        if (i + LPG * u < nparts) s4 += v[u];
     }
+    if (LPG == 4) {
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      s4[u] += __shfl_xor(s4[u], 1);
-      s4[u] += __shfl_xor(s4[u], 2);
+      for (int u = 0; u < 4; ++u) {
+        s4[u] += __shfl_xor(s4[u], 1);
+        s4[u] += __shfl_xor(s4[u], 2);
+      }
     }
     if (sub != 0 || e >= groups || q >= g.l || col >= g.n) continue;
     if (g.out_ek == EK_F32) {
@@ -694,8 +699,12 @@ static int launch_project_sum(hipStream_t s, const ProjectArgs& g) {
   const int64_t tiles = (int64_t)g.col_blocks * ceil_div64(g.l, g.bmq);
   const int groups = g.bmq * (g.bnx >> 2);
   // enough blocks per tile to occupy the machine, each thread at least one group
-  int bx = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(groups, 64), ceil_div64(4096, tiles)));
-  LORACT_LAUNCH("project_sum", s, project_sum_kernel, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, g);
+  // four lanes per group pay off when a tile has many partial tiles to walk through
+  const bool wide = g.wgs >= 8 * tiles;
+  const int gpb = wide ? 64 : 256;
+  int bx = (int)std::max<int64_t>(1, std::min<int64_t>(ceil_div64(groups, gpb), ceil_div64(4096, tiles)));
+  if (wide) LORACT_LAUNCH("project_sum", s, project_sum_kernel<4>, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, g);
+  else LORACT_LAUNCH("project_sum", s, project_sum_kernel<1>, dim3((unsigned)bx, (unsigned)tiles), dim3(256), 0, g);
   return LORACT_OK;
 }
 
