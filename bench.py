@@ -161,6 +161,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "coherent", "c5stream"])
     ap.add_argument("--layers", type=int, default=2,
                     help="c5stream only: decoder layers to stream (7 sites each; the full config is 32)")
+    ap.add_argument("--streams", type=int, default=3,
+                    help="independent sites in flight for the `pipelined` figure (hardware queues per process: 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-comparator", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
@@ -331,7 +333,7 @@ def main() -> int:
     # kernels of the others
     pipelined = None
     if not args.no_comparator:
-        nstreams = 3
+        nstreams = args.streams
         streams = [torch.cuda.Stream() for _ in range(nstreams)]
         held = []
         for _ in range(nstreams):
