@@ -136,10 +136,11 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_q1b = take(pl->bf16_path ? (size_t)m * pl->kp * 2 : 0);
   pl->off_nsT = take(pl->bf16_path ? (size_t)pl->kp * pl->kp * 2 : 0);
   pl->off_gbak = take(pl->bf16_path && pl->kp > 128 ? (size_t)pl->kp * pl->kp * 8 : 0);
-  pl->off_flag = take(64 + 8 * 64 * 16);   // flag word, then up to 64 x 15 shares of ||E||^2
+  pl->off_flag = take(64 + 8 * (64 * 16 + 128));   // flag word, up to 64 x 15 shares of ||E||^2, 100 of ||E^4||^2
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
+  if (pl->bf16_path) dpart = std::max(dpart, (size_t)pl->kp * pl->kp * 8);   // E^2 of the degree-4 finish
   pl->bgram_splits = 1;
   if (l > p->k) {
     pl->bgram_splits = pick_splits(lt * lt, n, 256);
@@ -258,6 +259,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   ch.shift_rel = 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16;
   ch.unshifted_thresh = chol_unshifted_thresh(l);
   ch.ns_e2 = nullptr; ch.ns_e2_count = 0; ch.ns_flag = nullptr; ch.ns_tol = 0.0; ch.ns_exact_tol = 0.0;
+  ch.poly_p4 = nullptr; ch.poly_count = 0; ch.poly_hi_tol = 0.0; ch.poly_b4_tol = 0.0;
   TrsmArgs t;
   t.L = G; t.Dinv = Dinv; t.m = m; t.kp = kp; t.k = l;
   // round 1: Q1 = Y R^{-1} (fp32, plus a bf16 copy for a possible Newton-Schulz finish)
@@ -273,6 +275,16 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   ch.round = 2;
   ch.ns_e2 = ns_e2; ch.ns_e2_count = 64 * gram_nblocks(kp); ch.ns_flag = ns_flag;
   ch.ns_tol = ns_ok ? 0.015 : 0.0;
+  // Tall matrices: when the first-order finish does not reach, a degree-4 correction is prepared
+  // (two small launches on k x k matrices, which return at once when they are not needed; they
+  // are only worth their fixed cost where a second factorisation and solve are expensive).
+  if (ns_ok && m >= 32768) {
+    NsPolyArgs np;
+    np.G = G; np.P2 = part; np.T = nsT; np.e2 = ns_e2; np.e2_count = ch.ns_e2_count;
+    np.p4 = ns_e2 + 64 * 16; np.k = l; np.kp = kp; np.lo_tol = ch.ns_tol; np.hi_tol = 2.0;
+    LORACT_TRY(launch_ns_poly(c.s, np));
+    ch.poly_p4 = np.p4; ch.poly_count = ns_poly_blocks(kp); ch.poly_hi_tol = np.hi_tol; ch.poly_b4_tol = 0.2;
+  }
   ch.ns_exact_tol = 1e-6;             // Q1 is then orthonormal to 1e-6 already: nothing for round 2 to do
   LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = tmp; t.Q = Q; t.ldq = l; t.out_ek = q_ek; t.out_cols = l; t.Qb = Qb; t.ldqb = l;

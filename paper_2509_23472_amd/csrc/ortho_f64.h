@@ -178,6 +178,8 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, in
       G[(int64_t)i * kp + j] = s;
       if (G_copy) G_copy[(int64_t)i * kp + j] = s;
       if (ns_e2) {
+        if (bi != bj) G[(int64_t)j * kp + i] = s;        // round 2 leaves the whole symmetric matrix
+
         double ev = 0.0;
         if (i < k && j < k) ev = s - (i == j ? 1.0 : 0.0);
         if (ns_T) {
@@ -265,6 +267,10 @@ struct CholArgs {
   int32_t* ns_flag;
   double ns_tol;            // Newton-Schulz finish up to this ||E||_F (0 = not available)
   double ns_exact_tol;      // Q1 accepted unchanged up to this ||E||_F
+  const double* poly_p4;    // optional: shares of ||E^4||_F^2 from ns_poly_finish_kernel
+  int poly_count;
+  double poly_hi_tol;       // the polynomial finish was attempted for ||E||_F in (ns_tol, poly_hi_tol]
+  double poly_b4_tol;       // ... and is accepted when ||E^4||_F^(1/4) (>= ||E||_2) is at most this
 };
 
 template <bool LDS_MODE>
@@ -315,6 +321,23 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
     if (g.ns_tol > 0.0 && tot <= g.ns_tol * g.ns_tol) {       // comparisons are false for NaN
       if (t == 0) *g.ns_flag = 1;
       return;
+    }
+    if (g.ns_tol > 0.0 && g.poly_count > 0 && tot <= g.poly_hi_tol * g.poly_hi_tol) {
+      // the degree-4 correction was prepared (T holds it): accept it if the spectral norm of E,
+      // bounded by ||E^4||_F^(1/4), keeps the truncated series accurate
+      if (wave == 0) {
+        double part_sum = 0.0;
+        for (int w = lane; w < g.poly_count; w += 64) part_sum += g.poly_p4[w];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
+        if (lane == 0) misc[2] = part_sum;
+      }
+      __syncthreads();
+      const double b4 = sqrt(sqrt(sqrt(misc[2])));
+      if (b4 <= g.poly_b4_tol) {
+        if (t == 0) *g.ns_flag = 1;
+        return;
+      }
     }
     if (t == 0) *g.ns_flag = 0;
   }
@@ -722,6 +745,115 @@ static int launch_trsm_nj_waves(hipStream_t s, const TrsmArgs& g) {
 template <int NJ>
 static int launch_trsm_nj(hipStream_t s, const TrsmArgs& g) {
   return g.m >= 32768 ? launch_trsm_nj_waves<NJ, 8>(s, g) : launch_trsm_nj_waves<NJ, 4>(s, g);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Higher-order finish of round 2.  With E = Q1^T Q1 - I symmetric and ||E||_2 < 1,
+//   (I + E)^(-1/2) = I - E/2 + 3 E^2/8 - 5 E^3/16 + 35 E^4/128 - ...,
+// so Q = Q1 (I + T) with T = -E/2 + 3 E^2/8 - 5 E^3/16 + 35 E^4/128 is orthonormal up to
+// ~ (63/128) ||E||_2^5: 1.6e-4 at ||E||_2 = 0.2.  The first-order step T = -E/2 only serves
+// ||E|| <= 0.015; with this one a sketch whose Gram matrix loses 14 digits (the long-context
+// sites) still needs no second factorisation and no second triangular solve over the m rows.
+// Two small launches on k x k matrices in float64: E^2, then E^3, E^4, T (bf16) and the shares of
+// ||E^4||_F^2, from which the factorisation kernel bounds ||E||_2 before it accepts T.
+// One 16 x 16 tile per wave.  The contraction index is dealt to the lanes in runs of four
+// (lane group q of an operand holds columns 16 kb + 4 q .. + 3), the same way for both operands,
+// so that every lane reads 32 contiguous bytes and a tile row is one 128-byte line; the second
+// operand is read by rows too, all matrices involved being symmetric.
+
+struct NsPolyArgs {
+  const double* G;          // Q1^T Q1, full symmetric kp x kp
+  double* P2;               // E^2 (kp x kp)
+  bf16_t* T;                // out: the correction, kp x kp bf16
+  const double* e2;         // shares of ||E||_F^2
+  int e2_count;
+  double* p4;               // out: one share of ||E^4||_F^2 per workgroup
+  int k, kp;
+  double lo_tol, hi_tol;    // active for ||E||_F in (lo_tol, hi_tol]
+};
+
+__device__ inline bool ns_poly_active(const NsPolyArgs& g, int lane) {
+  double part_sum = 0.0;
+  for (int w = lane; w < g.e2_count; w += 64) part_sum += g.e2[w];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
+  return part_sum > g.lo_tol * g.lo_tol && part_sum <= g.hi_tol * g.hi_tol;
+}
+
+// rows [16 t .. +15], four consecutive columns from c0 of E = G - I (live k x k part, else 0)
+__device__ inline f64x4 ns_poly_e4(const NsPolyArgs& g, int row, int c0) {
+  f64x4 v = *(const f64x4*)(g.G + (int64_t)row * g.kp + c0);
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    if (c0 + u == row) v[u] -= 1.0;
+    if (row >= g.k || c0 + u >= g.k) v[u] = 0.0;
+  }
+  return v;
+}
+
+__global__ __launch_bounds__(256) void ns_poly_square_kernel(NsPolyArgs g) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (!ns_poly_active(g, lane)) return;
+  const int nj = g.kp / 16;
+  const int tile = blockIdx.x * 4 + wave;
+  if (tile >= nj * nj) return;
+  const int ti = tile / nj, tj = tile - ti * nj;
+  const int lc = lane & 15, lr = lane >> 4;
+  f64x4 acc = (f64x4){0.0, 0.0, 0.0, 0.0};
+  for (int kb = 0; kb < nj; ++kb) {
+    const f64x4 a = ns_poly_e4(g, 16 * ti + lc, 16 * kb + 4 * lr);
+    const f64x4 b = ns_poly_e4(g, 16 * tj + lc, 16 * kb + 4 * lr);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) acc = mfma_f64(a[r], b[r], acc);
+  }
+#pragma unroll
+  for (int r = 0; r < 4; ++r) g.P2[(int64_t)(16 * ti + 4 * r + lr) * g.kp + 16 * tj + lc] = acc[r];
+}
+
+__global__ __launch_bounds__(256) void ns_poly_finish_kernel(NsPolyArgs g) {
+  __shared__ double red[4];
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  if (!ns_poly_active(g, lane)) return;          // uniform over the grid: every wave sums the same shares
+  const int nj = g.kp / 16;
+  const int tile = blockIdx.x * 4 + wave;
+  const bool on = tile < nj * nj;
+  const int ti = on ? tile / nj : 0, tj = on ? tile - ti * nj : 0;
+  const int lc = lane & 15, lr = lane >> 4;
+  f64x4 p3 = (f64x4){0.0, 0.0, 0.0, 0.0}, p4 = (f64x4){0.0, 0.0, 0.0, 0.0};
+  for (int kb = 0; kb < nj; ++kb) {
+    const f64x4 a = *(const f64x4*)(g.P2 + (int64_t)(16 * ti + lc) * g.kp + 16 * kb + 4 * lr);
+    const f64x4 be = ns_poly_e4(g, 16 * tj + lc, 16 * kb + 4 * lr);
+    const f64x4 bp = *(const f64x4*)(g.P2 + (int64_t)(16 * tj + lc) * g.kp + 16 * kb + 4 * lr);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      p3 = mfma_f64(a[r], be[r], p3);
+      p4 = mfma_f64(a[r], bp[r], p4);
+    }
+  }
+  double share = 0.0;
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int row = 16 * ti + 4 * r + lr, col = 16 * tj + lc;
+    double e = g.G[(int64_t)row * g.kp + col] - (row == col ? 1.0 : 0.0);
+    if (row >= g.k || col >= g.k) e = 0.0;
+    const double p2 = g.P2[(int64_t)row * g.kp + col];
+    const double tv = -0.5 * e + 0.375 * p2 - 0.3125 * p3[r] + 0.2734375 * p4[r];
+    if (on) g.T[(int64_t)row * g.kp + col] = (bf16_t)(float)tv;
+    if (on) share += p4[r] * p4[r];
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) share += __shfl_xor(share, off);
+  if (lane == 0) red[wave] = share;
+  __syncthreads();
+  if (threadIdx.x == 0) g.p4[blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+}
+
+static inline int ns_poly_blocks(int kp) { return ((kp / 16) * (kp / 16) + 3) / 4; }
+static int launch_ns_poly(hipStream_t s, const NsPolyArgs& g) {
+  const dim3 grid((unsigned)ns_poly_blocks(g.kp));
+  LORACT_LAUNCH("ns_poly_square", s, ns_poly_square_kernel, grid, dim3(256), 0, g);
+  LORACT_LAUNCH("ns_poly_finish", s, ns_poly_finish_kernel, grid, dim3(256), 0, g);
+  return LORACT_OK;
 }
 
 // ---------------------------------------------------------------------------------------------
