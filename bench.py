@@ -59,6 +59,9 @@ def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: i
         "gram": 2.0 * m * kp * kp * 0.75,        # lower 64-blocks only
         "trsm_apply": 1.0 * m * kp * kp + 2.0 * m * kp * 16,
         "chol": kp ** 3 / 3.0,
+        # degree-4 finish of round 2: E^2, then E^3 and E^4 (float64 products of kp x kp matrices)
+        "ns_poly_square": 2.0 * kp ** 3,
+        "ns_poly_finish": 4.0 * kp ** 3,
     }
     if name in flops:
         return "alu", flops[name], "TFLOP/s"

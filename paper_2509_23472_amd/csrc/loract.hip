@@ -135,7 +135,7 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_dinv = take((size_t)pl->kp * 16 * 8);
   pl->off_q1b = take(pl->bf16_path ? (size_t)m * pl->kp * 2 : 0);
   pl->off_nsT = take(pl->bf16_path ? (size_t)pl->kp * pl->kp * 2 : 0);
-  pl->off_gbak = take(pl->bf16_path && pl->kp > 128 ? (size_t)pl->kp * pl->kp * 8 : 0);
+  pl->off_gbak = take(pl->bf16_path ? (size_t)pl->kp * pl->kp * 8 : 0);
   pl->off_flag = take(64 + 8 * (64 * 16 + 128));   // flag word, up to 64 x 15 shares of ||E||^2, 100 of ||E^4||^2
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
@@ -248,7 +248,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   double* G = ws_ptr<double>(c, c.pl.off_g);
   double* Dinv = ws_ptr<double>(c, c.pl.off_dinv);
   double* part = ws_ptr<double>(c, c.pl.off_dpart);
-  double* Gbak = kp > 128 ? ws_ptr<double>(c, c.pl.off_gbak) : nullptr;
+  double* Gbak = ws_ptr<double>(c, c.pl.off_gbak);
   bf16_t* Q1b = ws_ptr<bf16_t>(c, c.pl.off_q1b);
   bf16_t* nsT = ws_ptr<bf16_t>(c, c.pl.off_nsT);
   int32_t* ns_flag = ws_ptr<int32_t>(c, c.pl.off_flag);

@@ -273,6 +273,51 @@ struct CholArgs {
   double poly_b4_tol;       // ... and is accepted when ||E^4||_F^(1/4) (>= ||E||_2) is at most this
 };
 
+// Round 2 decision, taken by the whole workgroup before any factorisation work: E = G - I has been
+// measured by gram_reduce_kernel (||E||_F^2 in pieces, T = -E/2 already written).  Returns true,
+// with *ns_flag set, when no second factorisation is needed; misc is an LDS scratch of 4 doubles.
+__device__ inline bool chol_round2_exit(const CholArgs& g, double* misc) {
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  // wave 0 adds the shares (lane i takes shares i, i + 64, ...; butterfly sum, so every lane
+  // ends with the same value) and hands the total to the other waves through LDS
+  if (wave == 0) {
+    double part_sum = 0.0;
+    for (int w = lane; w < g.ns_e2_count; w += 64) part_sum += g.ns_e2[w];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
+    if (lane == 0) misc[1] = part_sum;
+  }
+  __syncthreads();
+  const double tot = misc[1];
+  if (tot <= g.ns_exact_tol * g.ns_exact_tol) {     // Q1 is orthonormal as it stands
+    if (t == 0) *g.ns_flag = 2;
+    return true;
+  }
+  if (g.ns_tol > 0.0 && tot <= g.ns_tol * g.ns_tol) {       // comparisons are false for NaN
+    if (t == 0) *g.ns_flag = 1;
+    return true;
+  }
+  if (g.ns_tol > 0.0 && g.poly_count > 0 && tot <= g.poly_hi_tol * g.poly_hi_tol) {
+    // the degree-4 correction was prepared (T holds it): accept it if the spectral norm of E,
+    // bounded by ||E^4||_F^(1/4), keeps the truncated series accurate
+    if (wave == 0) {
+      double part_sum = 0.0;
+      for (int w = lane; w < g.poly_count; w += 64) part_sum += g.poly_p4[w];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
+      if (lane == 0) misc[2] = part_sum;
+    }
+    __syncthreads();
+    const double b4 = sqrt(sqrt(sqrt(misc[2])));
+    if (b4 <= g.poly_b4_tol) {
+      if (t == 0) *g.ns_flag = 1;
+      return true;
+    }
+  }
+  if (t == 0) *g.ns_flag = 0;
+  return false;
+}
+
 template <bool LDS_MODE>
 __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocked_kernel(CholArgs g) {
   constexpr int CHOL_THREADS = LDS_MODE ? CHOL_LDS_THREADS : 512;
@@ -300,47 +345,9 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   if (t == 0) { deficient = 0; restart = 0; }
   __syncthreads();
 
-  // ---- round 2: is Q1 already orthonormal enough for a Newton-Schulz finish?  gram_reduce_kernel
-  // has left ||E||_F^2 in pieces (and T = -E/2); on this branch the kernel ends here.
-  if (g.round == 2 && g.ns_flag) {
-    // wave 0 adds the shares (lane i takes shares i, i + 64, ...; butterfly sum, so every lane
-    // ends with the same value) and hands the total to the other waves through LDS
-    if (wave == 0) {
-      double part_sum = 0.0;
-      for (int w = lane; w < g.ns_e2_count; w += 64) part_sum += g.ns_e2[w];
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
-      if (lane == 0) misc[1] = part_sum;
-    }
-    __syncthreads();
-    const double tot = misc[1];
-    if (tot <= g.ns_exact_tol * g.ns_exact_tol) {     // Q1 is orthonormal as it stands
-      if (t == 0) *g.ns_flag = 2;
-      return;
-    }
-    if (g.ns_tol > 0.0 && tot <= g.ns_tol * g.ns_tol) {       // comparisons are false for NaN
-      if (t == 0) *g.ns_flag = 1;
-      return;
-    }
-    if (g.ns_tol > 0.0 && g.poly_count > 0 && tot <= g.poly_hi_tol * g.poly_hi_tol) {
-      // the degree-4 correction was prepared (T holds it): accept it if the spectral norm of E,
-      // bounded by ||E^4||_F^(1/4), keeps the truncated series accurate
-      if (wave == 0) {
-        double part_sum = 0.0;
-        for (int w = lane; w < g.poly_count; w += 64) part_sum += g.poly_p4[w];
-#pragma unroll
-        for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
-        if (lane == 0) misc[2] = part_sum;
-      }
-      __syncthreads();
-      const double b4 = sqrt(sqrt(sqrt(misc[2])));
-      if (b4 <= g.poly_b4_tol) {
-        if (t == 0) *g.ns_flag = 1;
-        return;
-      }
-    }
-    if (t == 0) *g.ns_flag = 0;
-  }
+  // ---- round 2: is Q1 already orthonormal enough for a Newton-Schulz finish?  On that branch
+  // the kernel ends here.
+  if (g.round == 2 && g.ns_flag && chol_round2_exit(g, misc)) return;
 
   if (LDS_MODE) {
     // kp is a multiple of 16: copy whole rows two doubles at a time
@@ -580,6 +587,402 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   }
   OF_STAMP(5);
   if (t == 0 && deficient && status) atomicOr(status, LORACT_STATUS_RANK_DEFICIENT);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Register-resident blocked Cholesky for kp <= 256: one workgroup of 8 waves, the matrix never
+// touches LDS or global memory between panels.
+//
+// Storage.  The symmetric matrix is kept as its UPPER 16 x 16 blocks U(C, I) = G[C rows][I cols],
+// C <= I, each in the accumulator layout of the float64 matrix instruction, dealt round-robin in
+// row-major order to the 7 worker waves (so every suffix C > j, the trailing matrix of panel j, and
+// every block row C == j, the panel itself, are spread evenly).  In that layout register r of a
+// block is at once slice r of the B operand of a product contracting over the block's rows, so
+//   panel j:     P_I^T = Linv_j U(j, I)            (P_I = L[I rows][j cols], 4 matrix instructions)
+//   trailing:    U(C, I) -= P_C P_I^T              (operands from LDS, accumulated in place)
+// need no layout change at all.  P^T goes to LDS (Pt) for the trailing update and to global
+// memory as L.  Within a block the rows are permuted: register r of lane group q holds row 4 q + r
+// (the hardware's natural order would be q + 4 r), so that a lane's four registers are 32
+// contiguous bytes of a row of G and the blocks are loaded with full cache lines; the permutation
+// is undone where it matters, in the row index of the A operand of the trailing update.
+//
+// Look-ahead.  Wave 0 owns the serial part.  While the workers apply panel j to the trailing
+// matrix, wave 0 takes the next diagonal block (staged in LDS by its owner one iteration earlier),
+// applies panel j to it, factors it one row per lane, and leaves L_bb and Linv_bb in LDS, from
+// where two workers copy them out.  Lanes 16..31 carry the rows of the identity through the same
+// 16 pivot steps, which turns them into the rows of L^{-T}: the inverse costs nothing extra.
+// Two workgroup barriers per panel; wave 0's pivot steps are the critical path and everything
+// else hides behind them once the trailing matrix is small enough.
+//
+// In round 1 the original matrix is read from G_backup (required: the unshifted attempt may have
+// to start over with the shift after L has begun to overwrite G), in round 2 from G.
+// Pivot rules, outputs (L in the strict lower triangle of G, Dinv) and the round-2 early exits are
+// those of chol_blocked_kernel, except that padding columns get a unit diagonal (their rows and
+// columns of L are zero either way).
+#define CR_THREADS 512
+#define CR_WORKERS 7
+
+static inline int chol_reg_ptld(int kp) {
+  const int w = kp > OF_NB ? kp - OF_NB : OF_NB;
+  return (w % 32 == 16) ? w : w + 16;        // consecutive panel rows start 128 bytes apart (mod 256)
+}
+// LDS doubles: misc[8] | LinvT[2][16][17] | Ltile[2][16][17] | Dstage[2][256] | Dtile[16][17] |
+//              Colbuf[2][64] | gdiag[kp] | Pt[16][ptld]
+static inline size_t chol_reg_lds_bytes(int kp) {
+  return sizeof(double) * (size_t)(8 + 544 + 544 + 512 + 272 + 128 + kp + OF_NB * chol_reg_ptld(kp));
+}
+
+template <int SLOTS>
+__global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int ptld) {
+  double* const G = g.G;
+  // (round 2 never starts over, and its caller's backup, if any, is round 1's matrix)
+  const double* const src = (g.round == 1 && g.G_backup) ? g.G_backup : g.G;
+  const int k = g.k, kp = g.kp, nb = kp / OF_NB;
+  extern __shared__ double smem[];
+  // (the fixed-size pieces come first, so that their addresses are compile-time constants)
+  double* misc = smem;                 // [0] trace, [1], [2] round-2 decision
+  double* LinvT = smem + 8;            // [b & 1][c * 17 + i] = Linv_bb[i][c]
+  double* Ltile = LinvT + 544;         // [b & 1][r * 17 + c] = L_bb[r][c]
+  double* Dstage = Ltile + 544;        // next diagonal blocks, accumulator layout, two buffers
+  double* Dtile = Dstage + 512;        // wave 0: diagonal block turned to one row per lane
+  double* Colbuf = Dtile + 272;        // wave 0: the two latest scaled columns of the diagonal block
+  double* gdiag = Colbuf + 128;        // original diagonal (wave 0 only)
+  double* Pt = gdiag + kp;             // Pt[p * ptld + x] = L[below + x][16 j + p]
+  __shared__ int deficient, restart;
+
+  const int t = threadIdx.x, lane = t & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(t >> 6);
+  const int lc = lane & 15, lr = lane >> 4;
+  const int pm = 4 * (lc & 3) + (lc >> 2);   // accumulator row of logical row lc, and back
+  if (t == 0) { deficient = 0; restart = 0; }
+  __syncthreads();
+  if (g.round == 2 && g.ns_flag && chol_round2_exit(g, misc)) return;
+
+  // ---- block ownership: worker w holds blocks e = s * 7 + w of the row-major upper triangle
+  // without block (0, 0), which wave 0 reads itself
+  // (packed as C | I << 8; an unused slot names block (0, 0), which no condition below selects)
+  int ci[SLOTS];
+  {
+    const int total = nb * (nb + 1) / 2 - 1;
+    int c = 0, rem = wave;                 // block e + 1 = rem-th of block row c, carried from slot to slot
+#pragma unroll
+    for (int s = 0; s < SLOTS; ++s) {
+      const int e = s * CR_WORKERS + wave - 1;
+      while (c < nb && rem >= nb - c) { rem -= nb - c; ++c; }
+      ci[s] = (wave > 0 && e < total) ? (c | ((c + rem) << 8)) : 0;
+      rem += CR_WORKERS;
+    }
+  }
+  // Unpacking goes through an empty volatile asm so that nothing derived from a slot's block
+  // coordinates is hoisted out of the panel loop (20 slots' worth of addresses would spill).
+#define CR_SLOT(s, C, I)                       \
+  int ci_ = ci[s];                             \
+  asm volatile("" : "+s"(ci_));                \
+  const int C = ci_ & 255, I = ci_ >> 8
+  // Block (C, I) as it lies in memory: lane (q, n) takes G[16 I + n][16 C + 4 q .. + 3]
+#define CR_LOAD_BLOCK(dst, C, I)                                                              \
+  {                                                                                           \
+    const double* p_ = src + (int64_t)(OF_NB * (I) + lc) * kp + OF_NB * (C) + 4 * lr;          \
+    const double2 v0_ = *(const double2*)p_, v1_ = *(const double2*)(p_ + 2);                  \
+    dst[0] = v0_.x; dst[1] = v0_.y; dst[2] = v1_.x; dst[3] = v1_.y;                            \
+  }
+  // Diagonal entries of a diagonal block: the shift, and 1 on the padding columns
+#define CR_FIX_DIAG(dst, C)                                                                   \
+  _Pragma("unroll") for (int r_ = 0; r_ < 4; ++r_)                                            \
+    if (4 * lr + r_ == lc) dst[r_] = (OF_NB * (C) + lc < k) ? dst[r_] + shift : 1.0;
+
+  // Round 1 starts with the unshifted attempt (the launcher sends anything else to
+  // chol_blocked_kernel), so the shift is needed on a second attempt only, long after wave 0 has
+  // left the trace in LDS.
+  const bool try_unshifted = g.round == 1;
+  for (int attempt = try_unshifted ? 0 : 1; attempt < 2; ++attempt) {
+    const bool unshifted_attempt = g.round == 1 && attempt == 0;
+    const double shift = (g.round == 1 && attempt == 1) ? g.shift_rel * misc[0] : 0.0;
+
+    // The two roles run separate loops with the same sequence of barriers, so that the workers'
+    // blocks and wave 0's pivot rows never compete for registers.
+    if (wave == 0) {
+      // ---- wave 0: factor diagonal block b, given in the accumulator layout
+      auto factor_diag = [&](const int b, const f64x4 dacc) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) Dtile[(4 * lr + r) * 17 + lc] = dacc[r];
+        __builtin_amdgcn_wave_barrier();      // LDS operations of one wave complete in order
+        double a[OF_NB];
+#define CR_LOAD_ROWS()                                                           \
+  _Pragma("unroll") for (int c = 0; c < OF_NB; ++c) {                            \
+    const double v = Dtile[lc * 17 + c];                                         \
+    a[c] = (lane < 16) ? v : ((lane < 32 && lc == c) ? 1.0 : 0.0);               \
+  }
+        CR_LOAD_ROWS();
+        // lane c: the level pivot c has to exceed (one rule for the three cases)
+        const double level = unshifted_attempt ? g.unshifted_thresh : (g.round == 1 ? 0.0 : g.tol);
+        const double thl = level * gdiag[OF_NB * b + lc];
+        // one opaque base register for all broadcast reads (otherwise every address becomes a
+        // hoisted constant of its own)
+        typedef const __attribute__((address_space(3))) double* lds_cptr;
+        unsigned colofs = (unsigned)(uintptr_t)(lds_cptr)Colbuf;
+        asm volatile("" : "+v"(colofs));
+        const lds_cptr colbase = (lds_cptr)(uintptr_t)colofs;
+
+        // ---- The 16 pivot steps, fast form.  One wave issues in order and a dependent float64
+        // operation costs it tens of cycles, so what counts is the number of DEPENDENT operations
+        // from one pivot to the next.  Here that chain is seven long and runs on wave-uniform
+        // values held in vector registers:
+        //   y = rsq(piv);  e = 1 - piv y^2;  q = e (1/2 + 3e/8)     (1/sqrt(piv) = y (1 + q))
+        //   l = l0 y (1 + q)        l0 = entry (jj+1, jj), read from its lane BEFORE the step
+        //   piv' = p0 - l^2         p0 = entry (jj+1, jj+1), likewise
+        // while the lanes scale their own row entry the same way (bitwise the same arithmetic as
+        // l) and apply the rank-1 update off the chain: columns jj+1 and jj+2 at once (with l and
+        // one lane read), the others one step later with multipliers read back from LDS (column
+        // jj is written there once scaled; one address for all lanes is a broadcast read).  Every
+        // column is therefore complete two steps before it holds the pivot, which is what allows
+        // l0 and p0 to be read early.  No operation on the chain tests the pivot: padding columns
+        // carry a unit diagonal, and a pivot that fails its test is only recorded (the block is
+        // then redone by the guarded form below).
+        bool any_bad = false;
+        {
+          double pivv = readlane_f64(a[0], 0);
+          double y = __builtin_amdgcn_rsq(pivv);
+#pragma unroll
+          for (int jj = 0; jj < OF_NB; ++jj) {
+            const bool live = OF_NB * b + jj < k;
+            any_bad = any_bad || (live && !(pivv > readlane_f64(thl, jj)));
+            double l0 = 0.0, p0 = 0.0;
+            if (jj + 1 < OF_NB) {
+              l0 = readlane_f64(a[jj], jj + 1);
+              p0 = readlane_f64(a[jj + 1], jj + 1);
+            }
+            double mult[OF_NB];
+            if (jj > 0) {
+              const lds_cptr col = colbase + ((jj - 1) & 1) * 64;
+#pragma unroll
+              for (int c = jj + 2; c < OF_NB; ++c) mult[c] = col[c];
+            }
+            const double s0 = a[jj] * y, ls0 = l0 * y;
+            const double tq = pivv * y;
+            const double eq = fma(-tq, y, 1.0);
+            const double q = eq * fma(0.375, eq, 0.5);
+            a[jj] = fma(s0, q, s0);
+            if (jj + 1 < OF_NB) {
+              const double l = fma(ls0, q, ls0);
+              pivv = fma(-l, l, p0);
+              y = __builtin_amdgcn_rsq(pivv);
+              a[jj + 1] = fma(-a[jj], l, a[jj + 1]);
+            }
+            Colbuf[(jj & 1) * 64 + lane] = a[jj];
+            if (jj + 2 < OF_NB) {
+              const double ln2 = readlane_f64(a[jj], jj + 2);
+              a[jj + 2] = fma(-a[jj], ln2, a[jj + 2]);
+            }
+            if (jj > 0) {
+#pragma unroll
+              for (int c = jj + 2; c < OF_NB; ++c) a[c] = fma(-a[jj - 1], mult[c], a[c]);
+            }
+          }
+        }
+        // ---- guarded form, only after a pivot failed its test (and the factorisation goes on:
+        // an unshifted attempt is abandoned anyway): unusable and padding columns get a zero
+        // reciprocal, so that they drop out of L and of Linv instead of spreading NaN.
+        if (any_bad && !unshifted_attempt) {
+          CR_LOAD_ROWS();
+          double piv = readlane_f64(a[0], 0);
+          double y = __builtin_amdgcn_rsq(piv);
+#pragma unroll
+          for (int jj = 0; jj < OF_NB; ++jj) {
+            const bool live = OF_NB * b + jj < k;
+            const bool usable = piv > readlane_f64(thl, jj);
+            const double tq = piv * y;
+            const double eq = fma(-tq, y, 1.0);
+            const double hq = y * fma(0.375, eq, 0.5);
+            const double d = (usable && live) ? fma(hq, eq, y) : 0.0;
+            a[jj] *= d;
+#pragma unroll
+            for (int c = jj + 1; c < OF_NB; ++c) {
+              const double lcj = readlane_f64(a[jj], c);
+              a[c] = fma(-a[jj], lcj, a[c]);
+            }
+            if (jj + 1 < OF_NB) {
+              piv = readlane_f64(a[jj + 1], jj + 1);
+              y = __builtin_amdgcn_rsq(piv);
+            }
+          }
+        }
+#undef CR_LOAD_ROWS
+        // lanes 0..15 hold the rows of L_bb, lanes 16..31 the rows of L_bb^{-T}: both to LDS, one
+        // store instruction per column (two workers copy them to global memory later)
+        if (lane < 32) {
+          double* base = ((lane < 16) ? Ltile : LinvT) + (b & 1) * 272 + lc * 17;
+#pragma unroll
+          for (int c = 0; c < OF_NB; ++c) base[c] = a[c];
+        }
+        if (lane == 0 && any_bad) {
+          if (unshifted_attempt) restart = 1; else deficient = 1;
+        }
+      };
+
+      __builtin_amdgcn_s_setprio(3);
+      {
+        // block (0, 0), and on the first pass the diagonal (pivot thresholds) with its sum (the
+        // shift of a second attempt), fetched in one memory round trip
+        f64x4 first;
+        if (attempt == 0 || !try_unshifted) {
+          double dg[4];
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int i = lane + 64 * q;
+            dg[q] = i < kp ? src[(int64_t)i * kp + i] : 0.0;
+          }
+          CR_LOAD_BLOCK(first, 0, 0);
+          double tr = 0.0;
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            if (lane + 64 * q < kp) gdiag[lane + 64 * q] = dg[q];
+            tr += dg[q];
+          }
+#pragma unroll
+          for (int off = 32; off > 0; off >>= 1) tr += __shfl_xor(tr, off);
+          if (lane == 0) misc[0] = tr;
+        } else {
+          CR_LOAD_BLOCK(first, 0, 0);
+        }
+        CR_FIX_DIAG(first, 0);
+        factor_diag(0, first);
+      }
+      __syncthreads();
+      // (the flag is made wave-uniform for the compiler)
+      for (int j = 0; j < nb - 1 && !__builtin_amdgcn_readfirstlane(restart); ++j) {
+#ifdef OF_TIMING
+        long long c0 = wall_clock64();
+#endif
+        __syncthreads();                      // panel j is in Pt
+#ifdef OF_TIMING
+        long long c1 = wall_clock64();
+#endif
+        const int b = j + 1;
+        f64x4 dacc;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) dacc[r] = Dstage[(b & 1) * 256 + r * 64 + lane];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          const double* prow = Pt + (4 * kk + lr) * ptld;
+          dacc = mfma_f64(-prow[pm], prow[lc], dacc);
+        }
+#ifdef OF_TIMING
+        long long c2 = wall_clock64();
+        asm volatile("" :: "v"(dacc));
+#endif
+        factor_diag(b, dacc);
+#ifdef OF_TIMING
+        long long c3 = wall_clock64();
+#endif
+        __syncthreads();                      // restart, if set, was written before this barrier
+#ifdef OF_TIMING
+        if (lane == 0) { of_stamps[20] += c1 - c0; of_stamps[21] += c2 - c1; of_stamps[22] += c3 - c2; of_stamps[23] += wall_clock64() - c3;
+                         if (j < 16) { of_stamps[32 + j] = c1 - c0; of_stamps[48 + j] = wall_clock64() - c3; } }
+#endif
+      }
+      __builtin_amdgcn_s_setprio(0);
+    } else {
+      // ---- workers load their blocks (all loads are issued before the first use)
+      f64x4 acc[SLOTS];
+#pragma unroll
+      for (int s = 0; s < SLOTS; ++s) {
+        CR_SLOT(s, C, I);
+        CR_LOAD_BLOCK(acc[s], C, I);
+      }
+#pragma unroll
+      for (int s = 0; s < SLOTS; ++s) {
+        CR_SLOT(s, C, I);
+        if (C == I) {
+          CR_FIX_DIAG(acc[s], C);
+          if (C == 1) {                       // wave 0 takes it after block (0, 0)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) Dstage[256 + r * 64 + lane] = acc[s][r];
+          }
+        }
+      }
+      // Block b's factors, left in LDS by wave 0, to global memory: Dinv by wave 1, L_bb by wave 2
+      auto copy_out = [&](const int b) {
+        if (wave == 1) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int e = lane + 64 * q;      // Dinv[b][c][i] = Linv[c][i] = LinvT[i][c]
+            g.Dinv[(int64_t)b * 256 + e] = LinvT[(b & 1) * 272 + (e & 15) * 17 + (e >> 4)];
+          }
+        } else if (wave == 2) {
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const int e = lane + 64 * q, r = e >> 4, c = e & 15;
+            if (c < r) G[(int64_t)(OF_NB * b + r) * kp + OF_NB * b + c] = Ltile[(b & 1) * 272 + r * 17 + c];
+          }
+        }
+      };
+      __syncthreads();
+      int jdone = -1;                         // last panel whose factors were copied out
+      for (int j = 0; j < nb - 1 && !__builtin_amdgcn_readfirstlane(restart); ++j) {
+        // ---- phase A: the rows of panel j, P_I^T = Linv_j U(j, I), to LDS and to L
+        double la[4];
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) la[kk] = LinvT[(j & 1) * 272 + (4 * lr + kk) * 17 + lc];
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+          CR_SLOT(s, C, I);
+          if (C == j && I > j) {
+            f64x4 d = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk) d = mfma_f64(la[kk], acc[s][kk], d);
+            const int x0 = OF_NB * (I - j - 1) + lc;
+            double* lrow = G + (int64_t)(OF_NB * I + lc) * kp + OF_NB * j + lr;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              Pt[(lr + 4 * r) * ptld + x0] = d[r];
+              lrow[4 * r] = d[r];
+            }
+          }
+        }
+        __syncthreads();
+
+        // ---- phase B: panel j applied to the trailing matrix (wave 0 factors block j + 1)
+        const int b = j + 1;
+#pragma unroll
+        for (int s = 0; s < SLOTS; ++s) {
+          CR_SLOT(s, C, I);
+          if (C > j && !(C == b && I == b)) {
+            const int xc = OF_NB * (C - j - 1) + pm, xi = OF_NB * (I - j - 1) + lc;
+            // The product is formed on its own and then subtracted: accumulating into acc[s]
+            // directly makes the compiler keep an old and a new copy of every block across this
+            // branch (the matrix instruction's destination may not overlap a live source).
+            f64x4 d = {0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int kk = 0; kk < 4; ++kk)
+              d = mfma_f64(Pt[(4 * kk + lr) * ptld + xc], Pt[(4 * kk + lr) * ptld + xi], d);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[s][r] -= d[r];
+            if (C == I && C == b + 1) {       // the diagonal block wave 0 takes next
+#pragma unroll
+              for (int r = 0; r < 4; ++r) Dstage[(C & 1) * 256 + r * 64 + lane] = acc[s][r];
+            }
+          }
+        }
+        copy_out(j);                          // its LDS copy is overwritten two panels later
+        jdone = j;
+        __syncthreads();
+      }
+      // the blocks not copied yet: the last one factored, and the one before it if the loop did
+      // not run for it (their LDS buffers differ)
+      if (!__builtin_amdgcn_readfirstlane(restart)) {
+        for (int b = jdone + 1; b < nb; ++b) copy_out(b);
+      }
+    }
+    if (!__builtin_amdgcn_readfirstlane(restart)) break;
+    __syncthreads();                          // everyone has seen the flag
+    if (t == 0) restart = 0;
+    __syncthreads();
+  }
+#undef CR_SLOT
+#undef CR_LOAD_BLOCK
+#undef CR_FIX_DIAG
+  if (t == 0 && deficient && g.status) atomicOr(g.status, LORACT_STATUS_RANK_DEFICIENT);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -955,6 +1358,18 @@ static inline double chol_unshifted_thresh(int k) { return 16.0 * (double)k * 1.
 
 static int launch_chol_blocked(hipStream_t s, CholArgs a) {
   a.tol = ((double)a.k * 5.9604644775390625e-08) * ((double)a.k * 5.9604644775390625e-08);
+#ifndef CHOL_NO_REG
+  if (a.kp <= 256 && (a.round == 2 || a.unshifted_thresh > 0.0)) {
+    if (a.round == 1 && !a.G_backup) return LORACT_ERR_INVALID_ARG;
+    const int ptld = chol_reg_ptld(a.kp);
+    const size_t lds = chol_reg_lds_bytes(a.kp);
+    if (a.kp <= 128)
+      LORACT_LAUNCH("chol", s, chol_reg_kernel<5>, dim3(1), dim3(CR_THREADS), lds, a, ptld);
+    else
+      LORACT_LAUNCH("chol", s, chol_reg_kernel<20>, dim3(1), dim3(CR_THREADS), lds, a, ptld);
+    return LORACT_OK;
+  }
+#endif
   if (a.kp <= 128) {
     const size_t lds = chol_lds_bytes(a.kp, true);
     if (lds > 64 * 1024 && !g_chol_lds_attr_set) {
