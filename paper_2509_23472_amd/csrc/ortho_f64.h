@@ -18,26 +18,10 @@
 #ifndef GRAM_TARGET_WGS
 #define GRAM_TARGET_WGS 256
 #endif
-#ifndef CHOL_LDS_THREADS
-#define CHOL_LDS_THREADS 256
-#endif
 #ifndef OF_RSQ_STEPS
 #define OF_RSQ_STEPS 1
 #endif
 
-// Phase timestamps for development harnesses; compiled out in the library build.
-#ifdef OF_SKIP
-__device__ int of_skip_mask;     // development harness only: bit 0 skips panels, bit 1 trailing updates
-#define OF_SKIPPED(bit) (of_skip_mask & (bit))
-#else
-#define OF_SKIPPED(bit) false
-#endif
-#ifdef OF_TIMING
-__device__ long long of_stamps[64];
-#define OF_STAMP(i) do { if (threadIdx.x == 0 && blockIdx.x == 0) of_stamps[i] = wall_clock64(); } while (0)
-#else
-#define OF_STAMP(i) do { } while (0)
-#endif
 
 __device__ inline f64x4 mfma_f64(double a, double b, f64x4 c) {
   return __builtin_amdgcn_mfma_f64_16x16x4f64(a, b, c, 0, 0, 0);
@@ -201,13 +185,14 @@ __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, in
 }
 
 // ---------------------------------------------------------------------------------------------
-// Blocked Cholesky factorisation G (+ shift) = L L^T of the kp x kp Gram matrix by one workgroup,
-// working in LDS when the matrix fits (kp <= 128) and in global memory otherwise.
+// Blocked Cholesky factorisation G (+ shift) = L L^T of the kp x kp Gram matrix by one workgroup.
+// Two kernels: chol_reg_kernel (further down: kp <= 256, matrix in registers, what the benchmark
+// shapes use) and chol_blocked_kernel (any kp, matrix updated in place in global memory).
 //
-// Per 16-column panel: every wave holds the 16 diagonal-block rows redundantly in lanes 0..15 and
-// up to 48 rows below in lanes 16..63, one row per lane with its 16 panel entries in registers;
-// the 16 pivot steps then need no workgroup barrier, only wave-wide lane reads.  The trailing
-// lower triangle is updated in 4 x 4 register tiles.
+// chol_blocked_kernel, per 16-column panel: every wave holds the 16 diagonal-block rows
+// redundantly in lanes 0..15 and up to 48 rows below in lanes 16..63, one row per lane with its 16
+// panel entries in registers; the 16 pivot steps then need no workgroup barrier, only wave-wide
+// lane reads.  The trailing lower triangle is updated per 16 x 16 block on the matrix cores.
 //
 // Outputs: L in the strict lower triangle of G (global), and Dinv[b] = inverse of the b-th
 // 16 x 16 diagonal block of L (row-major, lower triangular), which is what the triangular solve
@@ -238,13 +223,12 @@ __device__ inline double rsqrt_f64(double x) {
 }
 
 
-// LDS mode runs 4 waves (the pivot chains are latency bound, more waves only add contention);
-// global mode runs 8 waves to overlap the memory latency of the trailing-block updates.
+// chol_blocked_kernel runs 8 waves to overlap the memory latency of the trailing-block updates.
 //
 // round == 1 (Gram matrix of the sketch): the factorisation is first attempted WITHOUT a shift;
 //   a pivot that is not above unshifted_thresh * G[j][j] (a small multiple of the rounding level
 //   k u) abandons the attempt and the matrix is factored again as G + s I, s = shift_rel * trace
-//   (restored from G itself in LDS mode, from G_backup in global mode).  Unshifted factors leave
+//   (the matrix is restored from G_backup).  Unshifted factors leave
 //   Q1 = Y R^{-1} orthonormal to ~u cond(G); shifted ones only well conditioned (see chol.h).
 // round == 2 (Gram matrix of Q1): if ns_flag is given, E = G - I is measured first.  When
 //   ||E||_F <= ns_tol the factorisation is skipped (T = -E/2 was already written by
@@ -318,30 +302,25 @@ __device__ inline bool chol_round2_exit(const CholArgs& g, double* misc) {
   return false;
 }
 
-template <bool LDS_MODE>
-__global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocked_kernel(CholArgs g) {
-  constexpr int CHOL_THREADS = LDS_MODE ? CHOL_LDS_THREADS : 512;
+__global__ __launch_bounds__(512) void chol_blocked_kernel(CholArgs g) {
+  constexpr int CHOL_THREADS = 512;
   double* const G = g.G;
   double* const Dinv = g.Dinv;
   const int k = g.k, kp = g.kp;
   const double tol = g.tol;
   int32_t* const status = g.status;
   extern __shared__ double smem[];
-  // layout: gdiag[kp] | dinv[kp] | misc[8] | Pt[16][kp - 16] | (LDS mode) A[kp][kp + 2]
+  // layout: gdiag[kp] | dinv[kp] | misc[8] | Pt[16][kp - 16]
   double* gdiag = smem;            // original diagonal
   double* dinv = smem + kp;        // reciprocal pivots
   double* misc = smem + 2 * kp;    // [0] = shift
   const int ptld = kp > OF_NB ? kp - OF_NB : 2;
   double* Pt = smem + 2 * kp + 8;  // panel below the diagonal block, transposed: Pt[p][row - below]
-  double* Am = LDS_MODE ? (Pt + OF_NB * ptld) : G;
-  const int lda = LDS_MODE ? kp + 1 : kp;   // odd pitch: column walks hit distinct banks
+  double* Am = G;
+  const int lda = kp;
   __shared__ int deficient, restart;
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  OF_STAMP(0);
-#ifdef OF_TIMING
-  long long t_panel = 0, t_trail = 0, t_mark = 0, t_pl = 0, t_pc = 0, t_ps = 0, t_m2 = 0;
-#endif
   if (t == 0) { deficient = 0; restart = 0; }
   __syncthreads();
 
@@ -349,20 +328,8 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   // the kernel ends here.
   if (g.round == 2 && g.ns_flag && chol_round2_exit(g, misc)) return;
 
-  if (LDS_MODE) {
-    // kp is a multiple of 16: copy whole rows two doubles at a time
-    const int half = kp >> 1;
-#pragma unroll 8
-    for (int e = t; e < kp * half; e += CHOL_THREADS) {
-      const int i = e / half, j2 = e - i * half;
-      const double2 v = *(const double2*)(G + (int64_t)i * kp + 2 * j2);
-      Am[i * lda + 2 * j2] = v.x;
-      Am[i * lda + 2 * j2 + 1] = v.y;
-    }
-  }
   for (int i = t; i < kp; i += CHOL_THREADS) gdiag[i] = G[(int64_t)i * kp + i];
   __syncthreads();
-  OF_STAMP(1);
 
   double trace_sum = 0.0;
   if (wave == 0) {
@@ -374,7 +341,6 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   }
   __syncthreads();
   trace_sum = misc[0];
-  OF_STAMP(2);
 
   const bool try_unshifted = g.round == 1 && g.unshifted_thresh > 0.0;
   for (int attempt = try_unshifted ? 0 : 1; attempt < 2; ++attempt) {
@@ -382,25 +348,13 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
   const double shift = (g.round == 1 && attempt == 1) ? g.shift_rel * trace_sum : 0.0;
   if (attempt == 1 && try_unshifted) {
     // the unshifted attempt broke down: restore the matrix and start over with the shift
-    if (LDS_MODE) {
-      const int half = kp >> 1;
-      for (int e = t; e < kp * half; e += CHOL_THREADS) {
-        const int i = e / half, j2 = e - i * half;
-        const double2 v = *(const double2*)(G + (int64_t)i * kp + 2 * j2);
-        Am[i * lda + 2 * j2] = v.x;
-        Am[i * lda + 2 * j2 + 1] = v.y;
-      }
-    } else {
       for (int e = t; e < kp * kp; e += CHOL_THREADS) G[e] = g.G_backup[e];
-    }
+    
     if (t == 0) restart = 0;
     __syncthreads();
   }
 
   for (int jb = 0; jb < kp; jb += OF_NB) {
-#ifdef OF_TIMING
-    t_mark = wall_clock64();
-#endif
     const int below = jb + OF_NB;
     const int nrows_below = kp - below;
 
@@ -442,12 +396,8 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
       for (int c = 0; c < OF_NB; ++c)
         a[c] = (lane < 16) ? dsave[c] : (row_ok ? Am[row * lda + jb + c] : 0.0);
     }
-#ifdef OF_TIMING
-    { long long now = wall_clock64(); t_pl += now - t_mark; t_m2 = now; }
-#endif
     double dval[OF_NB];
     bool any_bad = false;
-    if (!OF_SKIPPED(1))
 #pragma unroll
     for (int j = 0; j < OF_NB; ++j) {
       const double piv = readlane_f64(a[j], j);
@@ -466,9 +416,6 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
         a[c] = fma(-a[j], lcj, a[c]);
       }
     }
-#ifdef OF_TIMING
-    { long long now = wall_clock64(); t_pc += now - t_m2; t_m2 = now; }
-#endif
     if (lane >= 16) {
       if (row_ok) {
 #pragma unroll
@@ -492,9 +439,6 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
     }
     __syncthreads();
     if (restart) break;          // uniform: written before the barrier
-#ifdef OF_TIMING
-    { long long now = wall_clock64(); t_ps += now - t_m2; t_panel += now - t_mark; t_mark = now; }
-#endif
 
     // ---- trailing update of the lower triangle: A[I][C] -= P_I P_C^T per 16 x 16 block (C <= I),
     // on the float64 matrix cores, the panel read from Pt.
@@ -506,7 +450,7 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
       // the first matrix instruction, so that their latency (LDS, or L2 when the matrix lives in
       // global memory) is paid once per trip.  The panel operands come from LDS at the point of use.
       constexpr int NWV = CHOL_THREADS / 64, TB = 4;
-      for (int e0 = wave; e0 < nblocks && !OF_SKIPPED(2); e0 += NWV * TB) {
+      for (int e0 = wave; e0 < nblocks; e0 += NWV * TB) {
         double* ablk[TB];
         int ta[TB], tb[TB];
         f64x4 acc[TB];
@@ -540,17 +484,10 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
       }
     }
     __syncthreads();
-#ifdef OF_TIMING
-    t_trail += wall_clock64() - t_mark;
-#endif
   }
   if (!restart) break;
   __syncthreads();
   }
-  OF_STAMP(3);
-#ifdef OF_TIMING
-  if (t == 0) { of_stamps[10] = t_panel; of_stamps[11] = t_trail; of_stamps[12] = t_pl; of_stamps[13] = t_pc; of_stamps[14] = t_ps; }
-#endif
 
   // ---- inverses of the 16 x 16 diagonal blocks, one thread per (block, column c):
   // column c of L_bb^{-1} by forward substitution in update form (x_j is final after step j and
@@ -572,20 +509,6 @@ __global__ __launch_bounds__(LDS_MODE ? CHOL_LDS_THREADS : 512) void chol_blocke
 #pragma unroll
     for (int r = 0; r < OF_NB; ++r) Dinv[((int64_t)b * OF_NB + r) * OF_NB + c] = x[r];
   }
-  OF_STAMP(4);
-  if (LDS_MODE) {
-    // the strict lower triangle is what consumers read; whole rows are copied back
-    const int half = kp >> 1;
-#pragma unroll 8
-    for (int e = t; e < kp * half; e += CHOL_THREADS) {
-      const int i = e / half, j2 = e - i * half;
-      double2 v;
-      v.x = Am[i * lda + 2 * j2];
-      v.y = Am[i * lda + 2 * j2 + 1];
-      *(double2*)(G + (int64_t)i * kp + 2 * j2) = v;
-    }
-  }
-  OF_STAMP(5);
   if (t == 0 && deficient && status) atomicOr(status, LORACT_STATUS_RANK_DEFICIENT);
 }
 
@@ -851,13 +774,7 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
       __syncthreads();
       // (the flag is made wave-uniform for the compiler)
       for (int j = 0; j < nb - 1 && !__builtin_amdgcn_readfirstlane(restart); ++j) {
-#ifdef OF_TIMING
-        long long c0 = wall_clock64();
-#endif
         __syncthreads();                      // panel j is in Pt
-#ifdef OF_TIMING
-        long long c1 = wall_clock64();
-#endif
         const int b = j + 1;
         f64x4 dacc;
 #pragma unroll
@@ -867,19 +784,8 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
           const double* prow = Pt + (4 * kk + lr) * ptld;
           dacc = mfma_f64(-prow[pm], prow[lc], dacc);
         }
-#ifdef OF_TIMING
-        long long c2 = wall_clock64();
-        asm volatile("" :: "v"(dacc));
-#endif
         factor_diag(b, dacc);
-#ifdef OF_TIMING
-        long long c3 = wall_clock64();
-#endif
         __syncthreads();                      // restart, if set, was written before this barrier
-#ifdef OF_TIMING
-        if (lane == 0) { of_stamps[20] += c1 - c0; of_stamps[21] += c2 - c1; of_stamps[22] += c3 - c2; of_stamps[23] += wall_clock64() - c3;
-                         if (j < 16) { of_stamps[32 + j] = c1 - c0; of_stamps[48 + j] = wall_clock64() - c3; } }
-#endif
       }
       __builtin_amdgcn_s_setprio(0);
     } else {
@@ -1343,13 +1249,9 @@ static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t 
   return LORACT_OK;
 }
 
-static bool g_chol_lds_attr_set = false;
-
-static size_t chol_lds_bytes(int kp, bool lds_mode) {
+static size_t chol_lds_bytes(int kp) {
   const int ptld = kp > OF_NB ? kp - OF_NB : 2;
-  size_t doubles = (size_t)2 * kp + 8 + (size_t)OF_NB * ptld;
-  if (lds_mode) doubles += (size_t)kp * (kp + 1);
-  return doubles * sizeof(double);
+  return sizeof(double) * ((size_t)2 * kp + 8 + (size_t)OF_NB * ptld);
 }
 
 // Breakdown level of the unshifted first-round attempt: 16 k u (pivots below it are within a
@@ -1358,9 +1260,8 @@ static inline double chol_unshifted_thresh(int k) { return 16.0 * (double)k * 1.
 
 static int launch_chol_blocked(hipStream_t s, CholArgs a) {
   a.tol = ((double)a.k * 5.9604644775390625e-08) * ((double)a.k * 5.9604644775390625e-08);
-#ifndef CHOL_NO_REG
+  if (a.round == 1 && a.unshifted_thresh > 0.0 && !a.G_backup) return LORACT_ERR_INVALID_ARG;
   if (a.kp <= 256 && (a.round == 2 || a.unshifted_thresh > 0.0)) {
-    if (a.round == 1 && !a.G_backup) return LORACT_ERR_INVALID_ARG;
     const int ptld = chol_reg_ptld(a.kp);
     const size_t lds = chol_reg_lds_bytes(a.kp);
     if (a.kp <= 128)
@@ -1369,21 +1270,7 @@ static int launch_chol_blocked(hipStream_t s, CholArgs a) {
       LORACT_LAUNCH("chol", s, chol_reg_kernel<20>, dim3(1), dim3(CR_THREADS), lds, a, ptld);
     return LORACT_OK;
   }
-#endif
-  if (a.kp <= 128) {
-    const size_t lds = chol_lds_bytes(a.kp, true);
-    if (lds > 64 * 1024 && !g_chol_lds_attr_set) {
-      hipError_t e = hipFuncSetAttribute((const void*)chol_blocked_kernel<true>,
-                                         hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024 - 1024);
-      if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(chol LDS)");
-      g_chol_lds_attr_set = true;
-    }
-    LORACT_LAUNCH("chol", s, chol_blocked_kernel<true>, dim3(1), dim3(CHOL_LDS_THREADS), lds, a);
-  } else {
-    if (a.round == 1 && a.unshifted_thresh > 0.0 && !a.G_backup) return LORACT_ERR_INVALID_ARG;
-    const size_t lds = chol_lds_bytes(a.kp, false);
-    LORACT_LAUNCH("chol", s, chol_blocked_kernel<false>, dim3(1), dim3(512), lds, a);
-  }
+  LORACT_LAUNCH("chol", s, chol_blocked_kernel, dim3(1), dim3(512), chol_lds_bytes(a.kp), a);
   return LORACT_OK;
 }
 

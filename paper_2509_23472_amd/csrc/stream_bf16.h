@@ -369,11 +369,6 @@ __device__ inline bf16x8 sb_pair_frag(const unsigned int* tile, int ldw, int p0,
 // contiguous share, writes one fp32 partial tile per output tile it touched, and
 // project_sum_kernel adds the partial tiles of each output tile in workgroup order.
 
-#ifdef PJ_ABLATE   // development harness only: bit 0 skips the copies, bit 1 the products, bit 2 the LDS reads
-#define PJ_SKIPPED(bit) ((PJ_ABLATE) & (bit))
-#else
-#define PJ_SKIPPED(bit) false
-#endif
 
 struct ProjectArgs {
   const bf16_t* Q;
@@ -465,7 +460,7 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
         const int ch = (lane % CX) ^ (2 * (row & 3));
         int64_t grow = r0 + row;
         if (grow > g.m - 1) grow = g.m - 1;
-        if (col0 + ch * 8 + 8 <= g.n && !PJ_SKIPPED(1))
+        if (col0 + ch * 8 + 8 <= g.n)
         {
           if (g.stream_x) sb_async16_stream(x_col + grow * g.ldx + ch * 8, st + (wave * XI + i) * 1024);
           else sb_async16(x_col + grow * g.ldx + ch * 8, st + (wave * XI + i) * 1024);
@@ -477,7 +472,7 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
         const int ch = (lane % CQ) ^ (2 * (row & 3));
         int64_t grow = r0 + row;
         if (grow > g.m - 1) grow = g.m - 1;
-        if (q0 + ch * 8 + 8 <= g.l && !PJ_SKIPPED(1))
+        if (q0 + ch * 8 + 8 <= g.l)
           sb_async16(q_col + grow * g.ldq + ch * 8, st + X_BYTES + (wave * QI + i) * 1024);
       }
     };
@@ -494,14 +489,14 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
     auto read_frags = [&](const unsigned char* st, int ks, s16x8* a, s16x8* b) {
 #pragma unroll
       for (int i = 0; i < NTQ; ++i) {
-        const s16x4 lo = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + q_off[i] + (16 * ks) * QPITCH);
-        const s16x4 hi = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + q_off[i] + (16 * ks + 4) * QPITCH);
+        const s16x4 lo = sb_read_tr(st + q_off[i] + (16 * ks) * QPITCH);
+        const s16x4 hi = sb_read_tr(st + q_off[i] + (16 * ks + 4) * QPITCH);
         a[i] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
 #pragma unroll
       for (int j = 0; j < NTX; ++j) {
-        const s16x4 lo = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + x_off[j] + (16 * ks) * XPITCH);
-        const s16x4 hi = PJ_SKIPPED(4) ? (s16x4){1, 1, 1, 1} : sb_read_tr(st + x_off[j] + (16 * ks + 4) * XPITCH);
+        const s16x4 lo = sb_read_tr(st + x_off[j] + (16 * ks) * XPITCH);
+        const s16x4 hi = sb_read_tr(st + x_off[j] + (16 * ks + 4) * XPITCH);
         b[j] = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
       }
     };
@@ -512,7 +507,6 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
 #pragma unroll
       for (int ks = 0; ks < 4; ++ks) {
         if (ks + 1 < 4) read_frags(st, ks + 1, a[(ks + 1) & 1], b[(ks + 1) & 1]);
-        if (!PJ_SKIPPED(2))
 #pragma unroll
         for (int i = 0; i < NTQ; ++i)
 #pragma unroll
@@ -559,7 +553,7 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
           const int qw = wm * 32 * NTQ + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-          if (q0 + qw < g.l && !(PJ_SKIPPED(8) && acc[i][j][r] == 0.0f)) dst[qw * BNX + colw] = acc[i][j][r];
+          if (q0 + qw < g.l) dst[qw * BNX + colw] = acc[i][j][r];
         }
       }
     ++seg;
@@ -737,11 +731,6 @@ static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = 
 
 #define RC_BM 64
 #define RC_LDV (128 + 4)     // words per pair-row of the V staging tile (128 columns at a time)
-#ifdef RC_ABLATE   // development harness only: bit 0 skips the U copies, bit 1 most stores, bit 2 the products
-#define RC_SKIPPED(bit) ((RC_ABLATE) & (bit))
-#else
-#define RC_SKIPPED(bit) false
-#endif
 
 struct ReconArgs {
   const bf16_t* U;       // m x k, ld = k
@@ -799,7 +788,7 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
         if (c < 0) c += CPR;
         int64_t grow = r0 + row;
         if (grow > g.m - 1) grow = g.m - 1;
-        if (c < cvalid && !RC_SKIPPED(1))
+        if (c < cvalid)
           sb_async16(g.U + grow * g.k + c * 8, Ub + buf * UBUF + ins * 1024);
       }
     }
@@ -901,7 +890,7 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
 #pragma unroll
         for (int u = 0; u < GS; ++u) {
           const int ks = GS * gi + u;
-          if (ks < NKS && !RC_SKIPPED(4)) {
+          if (ks < NKS) {
 #pragma unroll
             for (int j = 0; j < RH; ++j) {
               acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][0], b[gi & 1][u][j], acc[0][j], 0, 0, 0);
@@ -938,7 +927,7 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
           const int e = t + NT * (q0 + q);
           const int row = e / (BN / 8), ch = e % (BN / 8);
           const int64_t grow = r0 + row, col = col0 + ch * 8;
-          if (grow < g.m && col + 8 <= g.n && !(RC_SKIPPED(2) && it > 0)) {
+          if (grow < g.m && col + 8 <= g.n) {
             if (g.stream_out) __builtin_nontemporal_store(o[q], (bf16x8*)(g.Xhat + grow * g.ldxh + col));
             else *(bf16x8*)(g.Xhat + grow * g.ldxh + col) = o[q];
           }
