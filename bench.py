@@ -48,10 +48,10 @@ def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: i
         # reads U and the split G, writes T
         "lora_utg": m * k * fb + m * 2 * rp * 2 + k * 2 * rp * 4,
         "lora_vtt": k * n * fb + n * r * 4,
-        # Newton-Schulz finish: C = Q1b T (reads the bf16 copy of Q1 and T, writes C in fp32), then
-        # U = Q1 + C (reads both in fp32, writes U)
-        "ns_correct": m * kp * 2 + kp * kp * 2 + m * kp * 4,
-        "ns_finalize": 2 * m * kp * 4 + m * k * fb,
+        # Newton-Schulz finish, one kernel: U = Q1 + Q1b T (reads the bf16 copy of Q1, T and the
+        # fp32 Q1, writes U); the separate finalize kernel only runs for ranks not a multiple of 64
+        "ns_correct": m * kp * 2 + kp * kp * 2 + m * kp * 4 + m * k * fb,
+        "ns_finalize": m * kp * 4 + m * k * fb,
     }
     if name in hbm:
         return "hbm", float(hbm[name]), "GB/s"

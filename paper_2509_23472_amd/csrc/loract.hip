@@ -195,7 +195,7 @@ static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows
   const int l = c.pl.l;
   if (c.pl.bf16_path) {
     if (sb_aligned(c.X, c.p->ldx) && sb_aligned(Bt, ldb) && n % 64 == 0) {
-      SketchArgs a;
+      SketchArgs a{};
       a.X = (const bf16_t*)c.X; a.ldx = c.p->ldx; a.m = m; a.n = n;
       a.B = (const bf16_t*)Bt; a.ldb = ldb; a.b_rows = rows; a.l = l; a.kp = c.pl.kp;
       a.Y = (float*)Y; a.part = ws_ptr<float>(c, c.pl.off_fpart); a.splits = c.pl.sketch_splits;
@@ -291,15 +291,18 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   t.skip_flag = ns_flag;
   LORACT_TRY(launch_trsm_apply(c.s, t));
   if (ns_ok) {
-    SketchArgs a;                     // C = Q1b T^T  (T symmetric), into the free sketch buffer
-    a.X = Q1b; a.ldx = kp; a.m = m; a.n = kp; a.B = nsT; a.ldb = kp; a.b_rows = nullptr; a.l = kp; a.kp = kp;
-    a.Y = (float*)Y; a.part = nullptr; a.splits = 1; a.k_per_split = 0; a.run_flag = ns_flag;
-    a.ids_in_args = 0; a.clear_status = nullptr;
+    // Q = Q1 + Q1b T^T (T symmetric) for flag 1, Q = Q1 for flag 2, nothing for flag 0: the
+    // product kernel of the sketch with the finish fused into its epilogue
+    SketchArgs a{};
+    a.X = Q1b; a.ldx = kp; a.m = m; a.n = kp; a.B = nsT; a.ldb = kp; a.b_rows = nullptr; a.l = l; a.kp = kp;
+    a.Y = nullptr; a.part = nullptr; a.splits = 1; a.k_per_split = 0; a.run_flag = ns_flag;
+    a.fin_q1 = tmp; a.fin_q = Q; a.fin_qb = Qb; a.fin_ek = q_ek; a.fin_ld = l;
     LORACT_TRY(launch_sketch_mfma(c.s, a, "ns_correct"));
+  } else {
+    const int blocks = (int)std::min<int64_t>(ceil_div64(m * (kp / 4), 256), 2048);
+    LORACT_LAUNCH("ns_finalize", c.s, ns_finalize_kernel, dim3(blocks), dim3(256), 0, (const float*)tmp,
+                  (const float*)Y, m, kp, l, Q, q_ek, Qb, (const int32_t*)ns_flag);
   }
-  const int blocks = (int)std::min<int64_t>(ceil_div64(m * (kp / 4), 256), 2048);
-  LORACT_LAUNCH("ns_finalize", c.s, ns_finalize_kernel, dim3(blocks), dim3(256), 0, (const float*)tmp,
-                (const float*)Y, m, kp, l, Q, q_ek, Qb, (const int32_t*)ns_flag);
   return LORACT_OK;
 }
 
@@ -565,7 +568,7 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
       sb_aligned(U_dev, k) && sb_aligned(V_dev, n)) {
     const int rp = lp.rp;
     // G = dY B_lora^T (m x rp), the one pass over dY, left as the bf16 pair [G_hi | G_lo]
-    SketchArgs a;
+    SketchArgs a{};
     a.X = (const bf16_t*)dY_dev; a.ldx = n_out; a.m = m; a.n = n_out;
     a.B = (const bf16_t*)Blora_dev; a.ldb = n_out; a.b_rows = nullptr; a.l = r_lora; a.kp = rp;
     a.Y = (float*)(ws + lp.off_g); a.part = (float*)(ws + lp.off_gpart); a.splits = lp.g_splits;

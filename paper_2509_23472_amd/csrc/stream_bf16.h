@@ -126,6 +126,15 @@ struct SketchArgs {
   int stream_x;              // set by the launcher: X is too large to stay cached, copy it non-temporally
   int ids_in_args;           // the gather ids are `ids` below (read from the kernel-argument segment), not b_rows
   int32_t* clear_status;     // optional: word that the first workgroup sets to zero
+  // Optional fused finish (splits == 1 only).  With fin_q set the product is not stored: the
+  // launch writes fin_q (and its bf16 copy fin_qb, if given) = fin_q1 + X Bt^T, both with row
+  // pitch fin_ld and l valid columns, and run_flag selects 0: nothing, 1: as said, 2: no product,
+  // fin_q1 alone is converted.
+  const float* fin_q1;       // m x kp float32
+  void* fin_q;
+  bf16_t* fin_qb;
+  int fin_ek;                // EK_F32 or EK_BF16
+  int64_t fin_ld;
   IdxPack ids;
 };
 
@@ -138,7 +147,54 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
   constexpr int LOADS = 4 + NB;         // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
-  if (g.run_flag && *g.run_flag != 1) return;
+  const int run_mode = g.run_flag ? *g.run_flag : 1;
+  if (g.fin_q ? run_mode == 0 : run_mode != 1) return;
+  if (g.fin_q && run_mode == 2) {
+    // no product: the whole grid converts fin_q1, four columns per thread and step
+    const int64_t nthreads = (int64_t)gridDim.x * gridDim.y * gridDim.z * (128 * WM);
+    const int64_t tid = (((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * (128 * WM) + threadIdx.x;
+    const int c4 = g.kp >> 2;
+    const bool vec_ok = (g.fin_ld & 3) == 0 && ((uintptr_t)g.fin_q & 15) == 0 && ((uintptr_t)g.fin_qb & 7) == 0;
+    const int64_t total = g.m * c4;
+    // four independent loads in flight per thread: the grid is sized for the product, not for a copy
+    for (int64_t e0 = tid; e0 < total; e0 += 4 * nthreads) {
+      f32x4 q[4];
+      int64_t rr[4];
+      int cc[4];
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int64_t e = e0 + v * nthreads;
+        const int64_t ec = e < total ? e : tid;
+        rr[v] = total < (1ll << 31) ? (int64_t)((unsigned)ec / (unsigned)c4) : ec / c4;
+        cc[v] = (int)(ec - rr[v] * c4) << 2;
+        q[v] = *(const f32x4*)(g.fin_q1 + rr[v] * g.kp + cc[v]);
+      }
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        if (e0 + v * nthreads >= total) continue;
+        const int64_t r = rr[v];
+        const int c = cc[v];
+        if (vec_ok && c + 4 <= g.l) {
+          bf16x4 qh;
+#pragma unroll
+          for (int u = 0; u < 4; ++u) qh[u] = (bf16_t)q[v][u];
+          if (g.fin_ek == EK_F32) *(f32x4*)((float*)g.fin_q + r * g.fin_ld + c) = q[v];
+          else *(bf16x4*)((bf16_t*)g.fin_q + r * g.fin_ld + c) = qh;
+          if (g.fin_qb) *(bf16x4*)(g.fin_qb + r * g.fin_ld + c) = qh;
+          continue;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          if (c + u < g.l) {
+            if (g.fin_ek == EK_F32) ((float*)g.fin_q)[r * g.fin_ld + c + u] = q[v][u];
+            else ((bf16_t*)g.fin_q)[r * g.fin_ld + c + u] = (bf16_t)q[v][u];
+            if (g.fin_qb) g.fin_qb[r * g.fin_ld + c + u] = (bf16_t)q[v][u];
+          }
+        }
+      }
+    }
+    return;
+  }
   if (g.clear_status && threadIdx.x == 0 && blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0)
     *g.clear_status = 0;
   // ids carried in the arguments are read through the kernel-argument segment, which is ordinary
@@ -239,6 +295,32 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   }
 
   // epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
+  if (g.fin_q) {
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+      for (int j = 0; j < NT; ++j) {
+        const int col = col0 + wn * 32 * NT + 32 * j + (lane & 31);
+        if (col >= g.l) continue;
+        float q1[16];
+        int64_t rows[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          const int64_t row = row0 + wm * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          rows[r] = row;
+          q1[r] = g.fin_q1[(row < g.m ? row : g.m - 1) * g.kp + col];
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+          if (rows[r] >= g.m) continue;
+          const float q = q1[r] + acc[i][j][r];
+          if (g.fin_ek == EK_F32) ((float*)g.fin_q)[rows[r] * g.fin_ld + col] = q;
+          else ((bf16_t*)g.fin_q)[rows[r] * g.fin_ld + col] = (bf16_t)q;
+          if (g.fin_qb) g.fin_qb[rows[r] * g.fin_ld + col] = (bf16_t)q;
+        }
+      }
+    return;
+  }
   float* dst = g.splits > 1 ? g.part + (int64_t)zsplit * g.m * g.kp : g.Y;
 #pragma unroll
   for (int i = 0; i < 2; ++i)
@@ -303,7 +385,11 @@ static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const
 // [hi | lo] (m x 2 kp) instead of fp32 Y.
 static int launch_sketch_mfma(hipStream_t s, SketchArgs g, const char* name = "sketch",
                               bf16_t* split_out = nullptr) {
-  const int nt = sketch_nt_for(g.kp);
+  int nt = sketch_nt_for(g.kp);
+  // the fused finish contracts over kp only: with so little work per tile, narrower column tiles
+  // (more workgroups) win as long as the wide ones leave CUs idle
+  if (g.fin_q)
+    while (nt > 1 && ceil_div64(g.m, 128) * ceil_div64(g.kp, 64 * nt) < 256) nt >>= 1;
   g.stream_x = sb_streams_past_cache(g.m * g.n * 2);
   int64_t kps = ceil_div64(ceil_div64(g.n, g.splits), SB_BK) * SB_BK;
   g.splits = (int)ceil_div64(g.n, kps);
