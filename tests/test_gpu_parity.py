@@ -83,11 +83,14 @@ def test_bf16_small_and_ragged_shapes(m, n, k):
 
 
 @pytest.mark.parametrize("m,n,k", [(130, 64, 17), (1000, 512, 72), (4100, 1024, 136), (520, 640, 264),
-                                    (777, 320, 320), (129, 128, 128), (2048, 192, 8), (385, 448, 200)])
+                                    (777, 320, 320), (129, 128, 128), (2048, 192, 8), (385, 448, 200),
+                                    (1500, 512, 250), (600, 256, 16), (700, 256, 33)])
 def test_bf16_streaming_kernels_ragged_rows_and_all_rank_tiles(m, n, k):
     # n % 64 == 0 selects the matrix-core streaming kernels; the shapes walk through every
     # accumulator-tile variant (kp <= 64, <= 128, <= 256, two column blocks), the maximum rank,
-    # row counts that end inside a 128-row tile, and K ranges that do not divide evenly.
+    # row counts that end inside a 128-row tile, and K ranges that do not divide evenly; for the
+    # Cholesky kernels: one panel only (16), padding inside the last panel (33, 72, 136, 250), both
+    # register-resident sizes (<= 128, <= 256) and the in-place kernel above them (264, 320).
     w = _spectrum_workload(m, n, k, seed=7 * m + n + k, dtype="bf16", decay=0.93)
     x, u, v, xhat, status = _run(w)
     print(check_compress_parity(w, u, v, xhat))
