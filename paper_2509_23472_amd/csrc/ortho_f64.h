@@ -266,7 +266,15 @@ __device__ inline bool chol_round2_exit(const CholArgs& g, double* misc) {
   // ends with the same value) and hands the total to the other waves through LDS
   if (wave == 0) {
     double part_sum = 0.0;
-    for (int w = lane; w < g.ns_e2_count; w += 64) part_sum += g.ns_e2[w];
+    for (int w0 = lane; w0 < g.ns_e2_count; w0 += 256) {      // four loads in flight, no branch around them
+      double v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int w = w0 + 64 * u;
+        v[u] = g.ns_e2[w < g.ns_e2_count ? w : g.ns_e2_count - 1] * (w < g.ns_e2_count ? 1.0 : 0.0);
+      }
+      part_sum += (v[0] + v[1]) + (v[2] + v[3]);
+    }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
     if (lane == 0) misc[1] = part_sum;
@@ -749,18 +757,23 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
         // shift of a second attempt), fetched in one memory round trip
         f64x4 first;
         if (attempt == 0 || !try_unshifted) {
+          // (addresses are formed here, from a pitch the compiler cannot see through: hoisted out
+          // of the attempt loop they are spilled, and every reload then drains the load queue)
+          int kpo = kp;
+          asm volatile("" : "+s"(kpo));
           double dg[4];
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const int i = lane + 64 * q;
-            dg[q] = i < kp ? src[(int64_t)i * kp + i] : 0.0;
+          for (int q = 0; q < 4; ++q) {       // unconditional loads (a load under a branch is waited for on the spot)
+            const int i = lane + 64 * q, ic = i < kp ? i : kp - 1;
+            dg[q] = src[(int64_t)ic * kpo + ic];
           }
           CR_LOAD_BLOCK(first, 0, 0);
           double tr = 0.0;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            if (lane + 64 * q < kp) gdiag[lane + 64 * q] = dg[q];
-            tr += dg[q];
+          for (int q = 0; q < 4; ++q) {       // branch-free (a branch would pull the load into it): lanes
+            const int i = lane + 64 * q;      // past the end rewrite the last entry with its own value
+            gdiag[i < kp ? i : kp - 1] = dg[q];
+            tr += dg[q] * (i < kp ? 1.0 : 0.0);
           }
 #pragma unroll
           for (int off = 32; off > 0; off >>= 1) tr += __shfl_xor(tr, off);
