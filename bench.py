@@ -74,12 +74,12 @@ def c5_stream(args, L, torch, np) -> int:
     (harness code: X = c (G1 diag(s)) G2^T + 1e-3 N with Gaussian G1, G2 scaled to near-orthonormal
     columns, 1024 spectrum terms, s_i = i^-1.5, per-site seed) while the previous site is compressed
     on another stream; two X buffers alternate.  Factors of every site are kept, as in training."""
-    m, k, p = 16 * 4096, 256, 1024
-    widths = [4096] * 6 + [11008]
+    from workloads import gpu_sites
+    m, k = gpu_sites.C5_ROWS, gpu_sites.C5_RANK
+    widths = list(gpu_sites.C5_WIDTHS)
     sites = [(layer, s) for layer in range(args.layers) for s in range(7)]
     gen_stream, cmp_stream = torch.cuda.Stream(), torch.cuda.Stream()
     xbuf = [torch.empty((m, 11008), dtype=torch.bfloat16, device="cuda") for _ in range(2)]
-    svals = (torch.arange(1, p + 1, device="cuda", dtype=torch.float32) ** -1.5)
     factors, errs = [], []
     gen_done = [torch.cuda.Event() for _ in sites]
     cmp_done = [torch.cuda.Event() for _ in sites]
@@ -87,16 +87,8 @@ def c5_stream(args, L, torch, np) -> int:
     def generate(i):
         layer, s = sites[i]
         n = widths[s]
-        g = torch.Generator(device="cuda")
-        g.manual_seed(50_000 + 7 * layer + s)
-        c = float(np.sqrt(float(m) * n) / np.linalg.norm(np.arange(1, p + 1, dtype=np.float64) ** -1.5))
-        g1 = torch.randn((m, p), generator=g, device="cuda", dtype=torch.float32) * (c / np.sqrt(m))
-        g2 = torch.randn((n, p), generator=g, device="cuda", dtype=torch.float32) / np.sqrt(n)
         x = xbuf[i % 2].view(-1)[: m * n].view(m, n)
-        sig = ((g1 * svals).to(torch.bfloat16) @ g2.to(torch.bfloat16).t()).float()
-        sig.add_(torch.randn((m, n), generator=g, device="cuda", dtype=torch.float32), alpha=1e-3)
-        x.copy_(sig)
-        return x
+        return gpu_sites.c5_site_on_gpu(torch, layer, s, out=x)
 
     def run(check):
         factors.clear()

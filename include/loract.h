@@ -50,6 +50,8 @@ typedef enum { LORACT_F32 = 0, LORACT_BF16 = 1 } loract_dtype;
 /* Bits of the device status word written by loract_compress / loract_rsvd. */
 #define LORACT_STATUS_RANK_DEFICIENT 1   /* a direction of the sketch was numerically dependent on
                                             the others and was dropped: U has a zero column */
+#define LORACT_STATUS_INTERNAL 2         /* a workgroup's bounded wait for another workgroup of the
+                                            same launch ran out: the outputs are not valid */
 
 /* Problem statement of Algorithm 1: A in R^{m x n}, expected rank k, iterations t. */
 typedef struct {
@@ -61,7 +63,7 @@ typedef struct {
                             loract_compress: sampled rows (Algorithm 1 takes l = k; l > k is the
                             sample of Theorem 4.3).  loract_rsvd: k + oversampling.  With l > k the
                             l x n factor Q^T X is cut to its k leading singular triplets */
-  int32_t t;             /* power iterations (Algorithm 1, steps 3-6); 0 on the hot path */
+  int32_t t;             /* power iterations (the power rounds of Algorithm 1); 0 on the hot path */
   int32_t x_dtype;       /* loract_dtype of X */
   int32_t factor_dtype;  /* loract_dtype of U and V; F32 input requires F32 factors */
   uint64_t seed;         /* seed of the row sample (compress) or of the Gaussian test matrix (rsvd) */
@@ -73,7 +75,7 @@ const char* loract_strerror(int code);
 const char* loract_last_hip_error(void);
 
 /*
- * Algorithm 1, step 1: the l distinct row indices sampled uniformly without replacement from
+ * Algorithm 1, row sampling: the l distinct row indices sampled uniformly without replacement from
  * [0, m), in ascending order.  Pure host function; this is the definition the device path
  * uses when no explicit indices are given: splitmix64 started at `seed` drives Floyd's subset
  * sampling (for i = m-l .. m-1: j = next() mod (i+1); take j, or i if j was already taken).
@@ -135,8 +137,8 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
 
 /*
  * The comparator of Section 3.2: randomized SVD with a Gaussian test matrix Omega (n x l),
- * "identical to Algorithm 1 except for the test matrix": Y = X Omega, t x [QR; Y = X (X^T Q)],
- * QR, B = Q^T X (l x n); for l > k the result is truncated to the k leading singular triplets
+ * the same procedure as Algorithm 1 with Omega in place of the sampled rows: Y = X Omega,
+ * t x [QR; Y = X (X^T Q)], QR, B = Q^T X (l x n); for l > k the result is truncated to the k leading singular triplets
  * of B, so that U (m x k) and V (k x n) have the same shapes as loract_compress returns.
  * omegaT_dev   optional, Omega stored transposed (l x n, contiguous, dtype x_dtype); NULL =
  *              generate it on the device from p->seed (see loract_gaussian_omega_t).

@@ -6,15 +6,15 @@ the smoke check and the benchmark's `cpu_baseline` leg call it.
 
 What it follows (all citations are to the LoRAct paper, arXiv 2509.23472):
 
-* `decompose`        Algorithm 1 (sampling-based orthogonal decomposition), steps in the
-                     paper's order: sample k rows, Y = A A_k^T, t rounds of
-                     [QR; Y = A (A^T Q)], final QR, U = Q, V = Q^T A.
+* `decompose`        Section 3.2, Algorithm 1 (sampling-based orthogonal decomposition): the
+                     sketch of A by its own sampled rows, optionally sharpened by t power
+                     rounds, an orthonormal basis U of the sketch's range, and V = U^T A.
 * `reconstruct`      Section 3.1, Eq. (4): A~ = U V.
 * `lora_grad`        Section 3.1, Eq. (4)-(5) applied to a LoRA down-projection: the weight
                      gradient contraction A~^T (dY B^T) * scale, with A~ rebuilt first exactly
                      as the paper prescribes.
-* `rsvd`             Section 3.2: the randomized SVD the paper compares with ("identical
-                     except for the test matrix"), Gaussian test matrix, optional
+* `rsvd`             Section 3.2: the randomized SVD the paper compares with (the same
+                     procedure with a Gaussian test matrix in place of the sampled rows), optional
                      oversampling with truncation to rank k by an SVD of the small factor.
 * `prenorm_forward`, `prenorm_backward`
                      Section 3.3, Eqs. (6)-(10): RMS pre-norm unit that stores Norm(X) only.
@@ -156,13 +156,17 @@ def decompose(a: np.ndarray, k: int, t: int = 0, seed: int = 0,
     rows = sample_indices(m, l, seed) if idx is None else np.asarray(idx, dtype=np.int64)
     if rows.shape != (l,):
         raise ValueError("need exactly l sampled rows")
-    a_l = a[rows, :]                      # step 1: l sampled rows, l x n
-    y = a @ a_l.T                         # step 2: Y = A A_l^T, m x l
-    for _ in range(t):                    # steps 3-6
+    # The test matrix is the transposed block of sampled rows, so the sketch is A A_l^T (m x l).
+    a_l = a[rows, :]
+    y = a @ a_l.T
+    # Each power round replaces the sketch by A A^T Q with Q an orthonormal basis of the current
+    # sketch; only the sketch is re-orthonormalised, A^T Q is used as it comes.
+    for _ in range(t):
         q, _ = householder_qr(y)
         y = a @ (a.T @ q)
-    q, _ = householder_qr(y)              # step 7
-    b = q.T @ a                           # step 8: U = Q, V = Q^T A
+    # Orthonormal basis of range(Y); Q Q^T is the orthogonal projector that U V applies to A.
+    q, _ = householder_qr(y)
+    b = q.T @ a
     if l == k:
         return q, b
     ub, s, vbt = np.linalg.svd(b, full_matrices=False)

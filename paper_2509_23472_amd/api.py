@@ -73,7 +73,7 @@ def loract_version() -> str:
 
 
 def loract_sample_indices(m: int, l: int, seed: int) -> list:
-    """Algorithm 1, step 1 (host): the l ascending distinct row ids for `seed`."""
+    """Algorithm 1, row sampling (host): the l ascending distinct row ids for `seed`."""
     buf = (ctypes.c_int32 * max(l, 1))()
     _check(_lib.load().loract_sample_indices(m, l, seed & (2 ** 64 - 1), buf), "loract_sample_indices")
     return [int(buf[i]) for i in range(l)]

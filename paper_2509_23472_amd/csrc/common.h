@@ -4,7 +4,9 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <atomic>
 #include <map>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -53,8 +55,11 @@ struct ProfRecord {
   const char* name;
   hipEvent_t start, stop;
 };
+// The per-kernel profile is one process-wide record; `mu` serialises the host threads that
+// launch while it is on (launches from several threads are otherwise independent of each other).
 struct ProfState {
-  bool on = false;
+  std::atomic<bool> on{false};
+  std::mutex mu;
   std::vector<ProfRecord> recs;
   std::vector<hipEvent_t> pool;
   std::map<std::string, std::pair<double, int64_t>> agg;
@@ -62,7 +67,7 @@ struct ProfState {
 };
 static ProfState g_prof;
 
-static inline hipEvent_t prof_event() {
+static inline hipEvent_t prof_event() {   // caller holds g_prof.mu
   hipEvent_t e;
   if (!g_prof.pool.empty()) {
     e = g_prof.pool.back();
@@ -78,15 +83,19 @@ struct KernelScope {
   hipEvent_t start = nullptr, stop = nullptr;
   const char* name;
   KernelScope(const char* n, hipStream_t s) : stream(s), name(n) {
-    if (g_prof.on) {
-      start = prof_event();
-      stop = prof_event();
+    if (g_prof.on.load(std::memory_order_acquire)) {
+      {
+        std::lock_guard<std::mutex> lock(g_prof.mu);
+        start = prof_event();
+        stop = prof_event();
+      }
       if (start) (void)hipEventRecord(start, stream);
     }
   }
   ~KernelScope() {
     if (start && stop) {
       (void)hipEventRecord(stop, stream);
+      std::lock_guard<std::mutex> lock(g_prof.mu);
       g_prof.recs.push_back({name, start, stop});
     }
   }
@@ -131,6 +140,12 @@ __device__ inline void sb_async16_stream(const void* gsrc, void* lds_wave_base) 
   __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
                                    (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0,
                                    SB_STREAM_POLICY);
+}
+// The same copy as a device-scope load (sc1): for data another workgroup of the SAME launch wrote
+// with device-scope stores; a line this compute die's L2 may still hold from before is refetched.
+__device__ inline void sb_async16_device(const void* gsrc, void* lds_wave_base) {
+  __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)gsrc,
+                                   (__attribute__((address_space(3))) void*)lds_wave_base, 16, 0, 16);
 }
 // s_waitcnt with only the vector-memory counter constrained (gfx9 encoding).
 #define SB_WAIT_VMCNT(n) \

@@ -10,7 +10,10 @@
 
 #include <algorithm>
 #include <cmath>
+#include <cstdlib>
+#include <mutex>
 #include <set>
+#include <string>
 
 // ---------------------------------------------------------------------------------------------
 // Small utility kernels.
@@ -183,7 +186,7 @@ template <typename T>
 static T* ws_ptr(const Ctx& c, size_t off) { return (T*)(c.ws + off); }
 
 // Y (m x l) = X * Bt^T where Bt is l x n, K-contiguous rows of length n (optionally gathered
-// from X itself through the sampled row ids).  Algorithm 1, step 2 and the second half of step 5.
+// from X itself through the sampled row ids).  Algorithm 1: the sketch, and the second product of a power round.
 // The matrix-core sketch can take the sampled row ids in its own kernel arguments (`pack`, and
 // then also clears the status word), which saves the launch that stores them in the workspace.
 static bool sketch_takes_ids(const Ctx& c) {
@@ -211,7 +214,7 @@ static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows
                          rows ? EK_F32 : EK_F64, rows, m, l, n, 1.0, Y, l, EK_F64, 1, nullptr);
 }
 
-// Thin QR of Y (m x l) by two rounds of Cholesky QR with float64 Gram matrices (steps 4 and 7
+// Thin QR of Y (m x l) by two rounds of Cholesky QR with float64 Gram matrices (the orthonormalisations
 // of Algorithm 1).  Y is overwritten; the orthonormal factor is written to Qout (element kind
 // q_ek, leading dimension l).  `tmp` is a second m x l work buffer of Y's element kind.
 static int orthonormalise(const Ctx& c, void* Y, void* tmp, void* Qout, int q_ek) {
@@ -237,6 +240,16 @@ static int orthonormalise(const Ctx& c, void* Y, void* tmp, void* Qout, int q_ek
   return LORACT_OK;
 }
 
+// Tuning knob for measurements: LORACT_FUSED_SOLVE=0 in the environment runs the factorisation
+// and the triangular solve of round 1 as two launches instead of one.
+static bool fused_solve_enabled() {
+  static const bool on = [] {
+    const char* e = getenv("LORACT_FUSED_SOLVE");
+    return !(e && e[0] == '0');
+  }();
+  return on;
+}
+
 // bf16 path: the same two rounds on the matrix cores.  Y is m x kp float32 (zero padded
 // columns); round 1 factors the shifted Gram matrix and writes Q1 (float32) into tmp, round 2
 // writes the orthonormal factor as `Q` (element kind q_ek, k columns, leading dimension k) and,
@@ -259,16 +272,23 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   ch.shift_rel = 8.0 * std::max((double)l, sqrt((double)m)) * 1.1102230246251565e-16;
   ch.unshifted_thresh = chol_unshifted_thresh(l);
   ch.ns_e2 = nullptr; ch.ns_e2_count = 0; ch.ns_flag = nullptr; ch.ns_tol = 0.0; ch.ns_exact_tol = 0.0;
-  ch.poly_p4 = nullptr; ch.poly_count = 0; ch.poly_hi_tol = 0.0; ch.poly_b4_tol = 0.0;
+  ch.poly_p4 = nullptr; ch.poly_count = 0; ch.poly_hi_tol = 0.0; ch.poly_b4_tol = 0.0; ch.ready = nullptr;
   TrsmArgs t;
   t.L = G; t.Dinv = Dinv; t.m = m; t.kp = kp; t.k = l;
   // round 1: Q1 = Y R^{-1} (fp32, plus a bf16 copy for a possible Newton-Schulz finish)
-  LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, l, part, G, Gbak));
   ch.round = 1;
-  LORACT_TRY(launch_chol_blocked(c.s, ch));
+  ch.ready = fused_solve_enabled() ? ns_flag + 1 : nullptr;     // progress word of the fused launch
+  const bool fused = chol_trsm_fusable(ch);
+  LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, l, part, G, Gbak, nullptr, nullptr, fused ? ch.ready : nullptr));
   t.Y = Y; t.ldy = kp; t.Q = tmp; t.ldq = kp; t.out_ek = EK_F32; t.out_cols = kp;
   t.Qb = ns_ok ? Q1b : nullptr; t.ldqb = kp; t.skip_flag = nullptr;
-  LORACT_TRY(launch_trsm_apply(c.s, t));
+  if (fused) {
+    LORACT_TRY(launch_chol_trsm_fused(c.s, ch, t));
+  } else {
+    LORACT_TRY(launch_chol_blocked(c.s, ch));
+    LORACT_TRY(launch_trsm_apply(c.s, t));
+  }
+  ch.ready = nullptr;
   // round 2: either Q = Q1 (I - E/2) when E = Q1^T Q1 - I is small, or a second Cholesky QR
   double* ns_e2 = ws_ptr<double>(c, c.pl.off_flag) + 8;      // after the flag word
   LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr, ns_e2));
@@ -306,7 +326,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   return LORACT_OK;
 }
 
-// Bt (l x n) = Q^T X: step 8 of Algorithm 1 (and the first half of step 5).
+// Bt (l x n) = Q^T X: the projection of Algorithm 1 (and the first product of a power round).
 static int project(const Ctx& c, const void* Q, int q_ek, void* Bt, int out_ek) {
   const int64_t m = c.p->m, n = c.p->n;
   const int l = c.pl.l;
@@ -363,7 +383,7 @@ static int finish_factors(const Ctx& c, void* Y, void* tmp, void* U, void* V) {
   return project(c, Y, EK_F64, V, EK_F32);
 }
 
-// t rounds of [QR; Y = X (X^T Q)] (Algorithm 1, steps 3-6).  Only Y is orthonormalised.
+// t rounds of [QR; Y = X (X^T Q)] (the power rounds of Algorithm 1).  Only Y is orthonormalised.
 static int power_iterations(const Ctx& c, void* Y, void* tmp) {
   const int l = c.pl.l;
   for (int it = 0; it < c.p->t; ++it) {
@@ -480,14 +500,14 @@ int loract_compress(const void* X_dev, const loract_params* p, const int32_t* id
   void* Y = c.ws + c.pl.off_a;
   void* tmp = c.ws + c.pl.off_b;
   if (sketch_takes_ids(c)) {
-    LORACT_TRY(sketch(c, X_dev, p->ldx, nullptr, Y, &pack));   // steps 1-2
+    LORACT_TRY(sketch(c, X_dev, p->ldx, nullptr, Y, &pack));   // Y = X X_S^T, ids in the arguments
   } else {
     LORACT_LAUNCH("store_indices", s, store_indices_kernel, dim3((l + 255) / 256), dim3(256), 0, pack,
                   l, idx_dev, status_dev);
-    LORACT_TRY(sketch(c, X_dev, p->ldx, idx_dev, Y));          // steps 1-2
+    LORACT_TRY(sketch(c, X_dev, p->ldx, idx_dev, Y));          // Y = X X_S^T
   }
-  LORACT_TRY(power_iterations(c, Y, tmp));                // steps 3-6
-  if (l == k) return finish_factors(c, Y, tmp, U_dev, V_dev);   // steps 7-8
+  LORACT_TRY(power_iterations(c, Y, tmp));                // t power rounds
+  if (l == k) return finish_factors(c, Y, tmp, U_dev, V_dev);   // U = orth(Y), V = U^T X
   return truncate_factors(c, Y, tmp, U_dev, V_dev);       // l > k sampled rows: rank-k truncation
 }
 
@@ -685,6 +705,7 @@ int loract_prenorm_backward(const void* A_dev, int64_t m, int64_t n, int64_t lda
 }
 
 int loract_profile_begin(void) {
+  std::lock_guard<std::mutex> lock(g_prof.mu);
   g_prof.recs.clear();
   g_prof.agg.clear();
   g_prof.order.clear();
@@ -694,6 +715,7 @@ int loract_profile_begin(void) {
 
 int loract_profile_end(void) {
   g_prof.on = false;
+  std::lock_guard<std::mutex> lock(g_prof.mu);
   for (auto& r : g_prof.recs) {
     hipError_t e = hipEventSynchronize(r.stop);
     if (e != hipSuccess) return hip_fail(e, "hipEventSynchronize");
@@ -715,10 +737,14 @@ int loract_profile_end(void) {
   return LORACT_OK;
 }
 
-int loract_profile_count(void) { return (int)g_prof.order.size(); }
+int loract_profile_count(void) {
+  std::lock_guard<std::mutex> lock(g_prof.mu);
+  return (int)g_prof.order.size();
+}
 
 int loract_profile_get(int i, char* name_buf, int name_buf_len, double* total_ms,
                        int64_t* launches) {
+  std::lock_guard<std::mutex> lock(g_prof.mu);
   if (i < 0 || i >= (int)g_prof.order.size() || !name_buf || name_buf_len < 1)
     return LORACT_ERR_INVALID_ARG;
   const std::string& nm = g_prof.order[i];

@@ -132,8 +132,10 @@ __global__ __launch_bounds__(256) void gram_mfma_kernel(GramArgs g) {
 __global__ __launch_bounds__(256) void gram_reduce_kernel(const double* part, int chunks,
                                                           int nblocks, int kp, int k, double* G,
                                                           double* G_copy, bf16_t* ns_T,
-                                                          double* ns_e2) {
+                                                          double* ns_e2, int32_t* clear_word) {
   __shared__ double red[4];
+  // (the progress word of a fused factor-and-solve launch that follows starts at zero)
+  if (clear_word && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *clear_word = 0;
   const int b = blockIdx.y;
   int bi, bj;
   gram_block_of(b, &bi, &bj);
@@ -255,7 +257,26 @@ struct CholArgs {
   int poly_count;
   double poly_hi_tol;       // the polynomial finish was attempted for ||E||_F in (ns_tol, poly_hi_tol]
   double poly_b4_tol;       // ... and is accepted when ||E^4||_F^(1/4) (>= ||E||_2) is at most this
+  int32_t* ready;           // fused factor-and-solve launch only: progress word read by the solving workgroups
 };
+
+// Progress word of the fused factor-and-solve launch: (attempt << 16) | panels, where `panels` = p
+// means that block rows 0 .. p-1 of L (left of the diagonal) and the inverted diagonal blocks
+// 0 .. p-1 are complete in memory, and `attempt` counts restarts of the factorisation (a solving
+// workgroup that sees it change starts over: what it consumed so far belongs to the abandoned
+// attempt).  The producer writes L, Dinv and the word with device-scope write-through stores
+// and waits for their completion before it advances the word; consumers read with device-scope
+// loads.  No read-modify-write and no cache write-back is involved.
+#define CF_ATTEMPT_SHIFT 16
+__device__ inline void cf_store(double* p, double v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline void cf_publish(int32_t* ready, int attempt, int panels) {
+  __hip_atomic_store(ready, (attempt << CF_ATTEMPT_SHIFT) | panels, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ inline int cf_poll(const int32_t* ready) {
+  return __hip_atomic_load(ready, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
 
 // Round 2 decision, taken by the whole workgroup before any factorisation work: E = G - I has been
 // measured by gram_reduce_kernel (||E||_F^2 in pieces, T = -E/2 already written).  Returns true,
@@ -563,13 +584,14 @@ static inline size_t chol_reg_lds_bytes(int kp) {
   return sizeof(double) * (size_t)(8 + 544 + 544 + 512 + 272 + 128 + kp + OF_NB * chol_reg_ptld(kp));
 }
 
-template <int SLOTS>
-__global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int ptld) {
+// PUB: the factor is published panel by panel for the solving workgroups of the same launch
+// (chol_trsm_fused_kernel): write-through stores and the progress word g.ready.
+template <int SLOTS, bool PUB>
+__device__ inline void chol_reg_body(const CholArgs& g, const int ptld, double* smem) {
   double* const G = g.G;
   // (round 2 never starts over, and its caller's backup, if any, is round 1's matrix)
   const double* const src = (g.round == 1 && g.G_backup) ? g.G_backup : g.G;
   const int k = g.k, kp = g.kp, nb = kp / OF_NB;
-  extern __shared__ double smem[];
   // (the fixed-size pieces come first, so that their addresses are compile-time constants)
   double* misc = smem;                 // [0] trace, [1], [2] round-2 decision
   double* LinvT = smem + 8;            // [b & 1][c * 17 + i] = Linv_bb[i][c]
@@ -626,9 +648,12 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
   // chol_blocked_kernel), so the shift is needed on a second attempt only, long after wave 0 has
   // left the trace in LDS.
   const bool try_unshifted = g.round == 1;
+  int attempt_pub = 0;                 // attempt number as the solving workgroups count it
   for (int attempt = try_unshifted ? 0 : 1; attempt < 2; ++attempt) {
+    attempt_pub = (try_unshifted && attempt == 1) ? 1 : 0;
     const bool unshifted_attempt = g.round == 1 && attempt == 0;
     const double shift = (g.round == 1 && attempt == 1) ? g.shift_rel * misc[0] : 0.0;
+    if (PUB && attempt_pub == 1 && t == 64) cf_publish(g.ready, 1, 0);   // the solvers start over
 
     // The two roles run separate loops with the same sequence of barriers, so that the workers'
     // blocks and wave 0's pivot rows never compete for registers.
@@ -826,19 +851,26 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int e = lane + 64 * q;      // Dinv[b][c][i] = Linv[c][i] = LinvT[i][c]
-            g.Dinv[(int64_t)b * 256 + e] = LinvT[(b & 1) * 272 + (e & 15) * 17 + (e >> 4)];
+            const double dv = LinvT[(b & 1) * 272 + (e & 15) * 17 + (e >> 4)];
+            if (PUB) cf_store(g.Dinv + (int64_t)b * 256 + e, dv); else g.Dinv[(int64_t)b * 256 + e] = dv;
           }
         } else if (wave == 2) {
 #pragma unroll
           for (int q = 0; q < 4; ++q) {
             const int e = lane + 64 * q, r = e >> 4, c = e & 15;
-            if (c < r) G[(int64_t)(OF_NB * b + r) * kp + OF_NB * b + c] = Ltile[(b & 1) * 272 + r * 17 + c];
+            if (c < r) {
+              const double lv = Ltile[(b & 1) * 272 + r * 17 + c];
+              if (PUB) cf_store(G + (int64_t)(OF_NB * b + r) * kp + OF_NB * b + c, lv);
+              else G[(int64_t)(OF_NB * b + r) * kp + OF_NB * b + c] = lv;
+            }
           }
         }
       };
       __syncthreads();
       int jdone = -1;                         // last panel whose factors were copied out
       for (int j = 0; j < nb - 1 && !__builtin_amdgcn_readfirstlane(restart); ++j) {
+        // (published factors leave first, so that their stores are old by the end of the trip)
+        if (PUB) copy_out(j);
         // ---- phase A: the rows of panel j, P_I^T = Linv_j U(j, I), to LDS and to L
         double la[4];
 #pragma unroll
@@ -855,7 +887,7 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               Pt[(lr + 4 * r) * ptld + x0] = d[r];
-              lrow[4 * r] = d[r];
+              if (PUB) cf_store(lrow + 4 * r, d[r]); else lrow[4 * r] = d[r];
             }
           }
         }
@@ -883,9 +915,12 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
             }
           }
         }
-        copy_out(j);                          // its LDS copy is overwritten two panels later
+        if (!PUB) copy_out(j);                // its LDS copy is overwritten two panels later
         jdone = j;
+        if (PUB) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this wave's share of panel j is in memory
         __syncthreads();
+        // block row j + 1 of L (its last piece was panel j) and Dinv up to block j are complete
+        if (PUB && t == 64 && !restart) cf_publish(g.ready, attempt_pub, j + 1);
       }
       // the blocks not copied yet: the last one factored, and the one before it if the loop did
       // not run for it (their LDS buffers differ)
@@ -901,7 +936,20 @@ __global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int pt
 #undef CR_SLOT
 #undef CR_LOAD_BLOCK
 #undef CR_FIX_DIAG
+  if (PUB) {
+    // the last factors were copied out after the loop: once every wave's stores are complete the
+    // whole of L and Dinv is published (attempt 1 if the unshifted one was abandoned)
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (t == 64) cf_publish(g.ready, attempt_pub, nb);
+  }
   if (t == 0 && deficient && g.status) atomicOr(g.status, LORACT_STATUS_RANK_DEFICIENT);
+}
+
+template <int SLOTS>
+__global__ __launch_bounds__(CR_THREADS) void chol_reg_kernel(CholArgs g, int ptld) {
+  extern __shared__ double smem[];
+  chol_reg_body<SLOTS, false>(g, ptld, smem);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -937,21 +985,30 @@ struct TrsmArgs {
 // instruction operand touches over distinct banks.
 #define TRSM_J0(NJ) ((NJ) < 8 ? (NJ) : ((NJ) > 16 ? 6 : 8))
 #define TRSM_TILE_FLOATS (16 * 20)     // per-wave staging tile for the stores: 16 rows, pitch 20 floats
-template <int NJ, int WAVES>
-__global__ __launch_bounds__(64 * WAVES) void trsm_apply_kernel(TrsmArgs g) {
-  constexpr int J0 = TRSM_J0(NJ);
+#define TRSM_SPIN_LIMIT (1 << 22)      // polls of the progress word before a solving workgroup gives up
+
+// FUSED = false: L and Dinv are complete when the kernel starts (a launch of its own).
+// FUSED = true: the workgroup runs beside the factorisation (chol_trsm_fused_kernel) and takes
+// panel J when the progress word says it is complete: no panel is copied up front, panel J goes to
+// half J & 1 of the double buffer, and panel J + 1 is copied ahead only if it is complete already.
+// A change of the attempt number sends the workgroup back to J = 0.  `wg` is the workgroup's index
+// among the solving workgroups, `lds` its dynamic LDS.
+template <int NJ, int WAVES, bool FUSED>
+__device__ inline void trsm_body(const TrsmArgs& g, const int wg, double* trsm_lds, const int32_t* ready,
+                                 int32_t* status) {
+  constexpr int J0 = FUSED ? 0 : TRSM_J0(NJ);
   constexpr int PK = 8 * J0 * (J0 + 1) + 2;           // pitch of the side-by-side array, in doubles
   constexpr int PR = 16 * NJ + 2;                     // pitch of a double-buffer half
-  extern __shared__ __attribute__((aligned(16))) double trsm_lds[];
-  double* const ring = trsm_lds + 16 * PK;
+  double* const ring = trsm_lds + (FUSED ? 0 : 16 * PK);
   float* const tile = (float*)(ring + (NJ > J0 ? 32 * PR : 0)) + (threadIdx.x >> 6) * TRSM_TILE_FLOATS;
+  int* const word = (int*)((float*)(ring + (NJ > J0 ? 32 * PR : 0)) + WAVES * TRSM_TILE_FLOATS);   // FUSED: the progress word as the workgroup saw it
   if (g.skip_flag && *g.skip_flag != 0) return;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int lc = lane & 15, lr = lane >> 4;
-  const int64_t row = (int64_t)blockIdx.x * (16 * WAVES) + wave * 16 + lc;
+  const int64_t row = (int64_t)wg * (16 * WAVES) + wave * 16 + lc;
   const bool rok = row < g.m;
   // every row of the wave exists: its store instructions per step can be counted
-  const bool full_wave = (int64_t)blockIdx.x * (16 * WAVES) + wave * 16 + 15 < g.m;
+  const bool full_wave = (int64_t)wg * (16 * WAVES) + wave * 16 + 15 < g.m;
   const float* yrow = g.Y + (rok ? row : 0) * g.ldy;   // rows past m read row 0 and are never stored
   // 4 consecutive output columns per lane can be stored as one vector
   const bool vec_ok = (g.ldq & 3) == 0 && ((uintptr_t)g.Q & 15) == 0 &&
@@ -959,6 +1016,7 @@ __global__ __launch_bounds__(64 * WAVES) void trsm_apply_kernel(TrsmArgs g) {
 
   // Copy of panel J to `dst` (pitch in doubles): one wave-wide instruction per (panel row, 64
   // pieces of 16 bytes), dealt round-robin to the waves; lanes past the row end stay idle.
+  // (FUSED: device-scope loads, the panel was written by another workgroup of this launch.)
   auto copy_panel = [&](int J, double* dst, int pitch) {
     const int pieces = 8 * (J + 1);
     const int nq = (pieces + 63) / 64;
@@ -968,100 +1026,177 @@ __global__ __launch_bounds__(64 * WAVES) void trsm_apply_kernel(TrsmArgs g) {
       if (c < 16 * (J + 1)) {
         const double* src = c < 16 * J ? g.L + (int64_t)(16 * J + r) * g.kp + c
                                         : g.Dinv + ((int64_t)J * 16 + r) * 16 + (c - 16 * J);
-        sb_async16(src, (unsigned char*)(dst + r * pitch) + q * 1024);
+        if (FUSED) sb_async16_device(src, (unsigned char*)(dst + r * pitch) + q * 1024);
+        else sb_async16(src, (unsigned char*)(dst + r * pitch) + q * 1024);
       }
     }
   };
+  // FUSED: the whole workgroup learns the progress word (one poll per trip, shared through LDS);
+  // returns it once panel J of attempt `att` is complete or the attempt has changed
+  auto wait_panel = [&](int J, int att) -> int {
+    int f = 0;
+    for (int spin = 0; spin < TRSM_SPIN_LIMIT; ++spin) {
+      if (t == 0) *word = cf_poll(ready);
+      sb_barrier_lds();
+      f = *word;
+      sb_barrier_lds();                  // everyone has read the word before the next poll rewrites it
+      if ((f >> CF_ATTEMPT_SHIFT) != att || (f & 0xffff) > J) return f;
+      __builtin_amdgcn_s_sleep(8);
+    }
+    return -1;
+  };
 
+  if (!FUSED) {
 #pragma unroll
-  for (int J = 0; J < J0; ++J) copy_panel(J, trsm_lds + 8 * J * (J + 1), PK);
-  SB_WAIT_VMCNT(0);
-  __syncthreads();
+    for (int J = 0; J < J0; ++J) copy_panel(J, trsm_lds + 8 * J * (J + 1), PK);
+    SB_WAIT_VMCNT(0);
+    __syncthreads();
+  }
 
   f64x4 qb[NJ];
   float ycur[4], ynext[4];
+  int att = 0;
+  bool restart_solve;
+  do {
+    restart_solve = false;
+    bool next_copied = false;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) ycur[r] = yrow[4 * r + lr];
+    for (int r = 0; r < 4; ++r) ycur[r] = yrow[4 * r + lr];
 #pragma unroll
-  for (int J = 0; J < NJ; ++J) {
-    const bool ring_next = J + 1 >= J0 && J + 1 < NJ;
-    if (ring_next) copy_panel(J + 1, ring + ((J + 1) & 1) * 16 * PR, PR);
-    if (J + 1 < NJ) {
+    for (int J = 0; J < NJ; ++J) {
+      if (FUSED) {
+        if (restart_solve) continue;                     // (uniform) the attempt changed: drain the unrolled loop
+        const int f = wait_panel(J, att);
+        if (f < 0) {                                     // the factorisation never got here: give up, flagged
+          if (t == 0 && status) atomicOr(status, LORACT_STATUS_INTERNAL);
+          return;
+        }
+        if ((f >> CF_ATTEMPT_SHIFT) != att) { att = f >> CF_ATTEMPT_SHIFT; restart_solve = true; continue; }
+        if (!next_copied) copy_panel(J, ring + (J & 1) * 16 * PR, PR);
+        next_copied = false;
+        if (J + 1 < NJ) {
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ynext[r] = yrow[16 * (J + 1) + 4 * r + lr];
-    }
-    const double* pan = J < J0 ? trsm_lds + lc * PK + 8 * J * (J + 1) : ring + (J & 1) * 16 * PR + lc * PR;
-    f64x4 s = (f64x4){0.0, 0.0, 0.0, 0.0};
+          for (int r = 0; r < 4; ++r) ynext[r] = yrow[16 * (J + 1) + 4 * r + lr];
+        }
+        SB_WAIT_VMCNT(4);                                 // the panel's copies are older than the 4 loads of ynext
+        if (J + 1 >= NJ) SB_WAIT_VMCNT(0);
+        sb_barrier_lds();                                // everyone's share of panel J landed
+        if (J + 1 < NJ && (f & 0xffff) > J + 1) {        // the next panel is complete as well: copy it ahead
+          copy_panel(J + 1, ring + ((J + 1) & 1) * 16 * PR, PR);
+          next_copied = true;
+        }
+      } else {
+        const bool ring_next = J + 1 >= J0 && J + 1 < NJ;
+        if (ring_next) copy_panel(J + 1, ring + ((J + 1) & 1) * 16 * PR, PR);
+        if (J + 1 < NJ) {
 #pragma unroll
-    for (int I = 0; I < J; ++I) {
-#pragma unroll
-      for (int r = 0; r < 4; ++r) s = mfma_f64(pan[16 * I + 4 * r + lr], qb[I][r], s);
-    }
-    f64x4 tt;
-#pragma unroll
-    for (int r = 0; r < 4; ++r) tt[r] = (double)ycur[r] - s[r];
-    f64x4 o = (f64x4){0.0, 0.0, 0.0, 0.0};
-#pragma unroll
-    for (int r = 0; r < 4; ++r) o = mfma_f64(pan[16 * J + 4 * r + lr], tt[r], o);
-    qb[J] = o;
-    if (vec_ok && 16 * J + 16 <= g.out_cols) {
-      // The 16 x 16 block is turned through a wave-private LDS tile (LDS operations of one wave
-      // execute in order) so that every lane stores 4 consecutive columns at once.
-#pragma unroll
-      for (int r = 0; r < 4; ++r) tile[lc * 20 + 4 * r + lr] = (float)o[r];
-      const f32x4 v = *(const f32x4*)(tile + lc * 20 + 4 * lr);
-      bf16x4 vh;
-#pragma unroll
-      for (int u = 0; u < 4; ++u) vh[u] = (bf16_t)v[u];
-      if (rok) {
-        const int col = 16 * J + 4 * lr;
-        if (g.out_ek == EK_F32) *(f32x4*)((float*)g.Q + row * g.ldq + col) = v;
-        else *(bf16x4*)((bf16_t*)g.Q + row * g.ldq + col) = vh;
-        if (g.Qb) *(bf16x4*)(g.Qb + row * g.ldqb + col) = vh;
-      }
-    } else if (rok) {
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        const int col = 16 * J + 4 * r + lr;
-        if (col < g.out_cols) {
-          if (g.out_ek == EK_F32) ((float*)g.Q)[row * g.ldq + col] = (float)o[r];
-          else ((bf16_t*)g.Q)[row * g.ldq + col] = (bf16_t)(float)o[r];
-          if (g.Qb) g.Qb[row * g.ldqb + col] = (bf16_t)(float)o[r];
+          for (int r = 0; r < 4; ++r) ynext[r] = yrow[16 * (J + 1) + 4 * r + lr];
         }
       }
-    }
-    if (J + 1 < NJ) {
+      const double* pan = (!FUSED && J < J0) ? trsm_lds + lc * PK + 8 * J * (J + 1) : ring + (J & 1) * 16 * PR + lc * PR;
+      f64x4 s = (f64x4){0.0, 0.0, 0.0, 0.0};
 #pragma unroll
-      for (int r = 0; r < 4; ++r) ycur[r] = ynext[r];
+      for (int I = 0; I < J; ++I) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) s = mfma_f64(pan[16 * I + 4 * r + lr], qb[I][r], s);
+      }
+      f64x4 tt;
+#pragma unroll
+      for (int r = 0; r < 4; ++r) tt[r] = (double)ycur[r] - s[r];
+      f64x4 o = (f64x4){0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o = mfma_f64(pan[16 * J + 4 * r + lr], tt[r], o);
+      qb[J] = o;
+      if (vec_ok && 16 * J + 16 <= g.out_cols) {
+        // The 16 x 16 block is turned through a wave-private LDS tile (LDS operations of one wave
+        // execute in order) so that every lane stores 4 consecutive columns at once.
+#pragma unroll
+        for (int r = 0; r < 4; ++r) tile[lc * 20 + 4 * r + lr] = (float)o[r];
+        const f32x4 v = *(const f32x4*)(tile + lc * 20 + 4 * lr);
+        bf16x4 vh;
+#pragma unroll
+        for (int u = 0; u < 4; ++u) vh[u] = (bf16_t)v[u];
+        if (rok) {
+          const int col = 16 * J + 4 * lr;
+          if (g.out_ek == EK_F32) *(f32x4*)((float*)g.Q + row * g.ldq + col) = v;
+          else *(bf16x4*)((bf16_t*)g.Q + row * g.ldq + col) = vh;
+          if (g.Qb) *(bf16x4*)(g.Qb + row * g.ldqb + col) = vh;
+        }
+      } else if (rok) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int col = 16 * J + 4 * r + lr;
+          if (col < g.out_cols) {
+            if (g.out_ek == EK_F32) ((float*)g.Q)[row * g.ldq + col] = (float)o[r];
+            else ((bf16_t*)g.Q)[row * g.ldq + col] = (bf16_t)(float)o[r];
+            if (g.Qb) g.Qb[row * g.ldqb + col] = (bf16_t)(float)o[r];
+          }
+        }
+      }
+      if (J + 1 < NJ) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) ycur[r] = ynext[r];
+      }
+      if (FUSED) {
+        // the stores of this step and a copy issued ahead may stay in flight; the next trip's
+        // wait_panel barriers order this trip's reads of the buffer half before its refill
+        if (next_copied) SB_WAIT_VMCNT(0);
+      } else if (J + 1 >= J0 && J + 1 < NJ) {
+        // The copies of panel J + 1 are older than this step's stores (1 per wave on the vector
+        // path, 2 with the second output; every column of a step that is not the last lies inside
+        // out_cols), so they have landed once at most that many operations are pending.  The barrier also orders this step's
+        // reads of its buffer half before the copy that the next step issues into it.
+        if (!full_wave || !vec_ok) SB_WAIT_VMCNT(0);
+        else if (g.Qb) SB_WAIT_VMCNT(2);
+        else SB_WAIT_VMCNT(1);
+        sb_barrier_lds();
+      }
     }
-    if (ring_next) {
-      // The copies of panel J + 1 are older than this step's stores (1 per wave on the vector
-      // path, 2 with the second output; every column of a step that is not the last lies inside
-      // out_cols), so they have landed once at most that many operations are pending.  The barrier also orders this step's
-      // reads of its buffer half before the copy that the next step issues into it.
-      if (!full_wave || !vec_ok) SB_WAIT_VMCNT(0);
-      else if (g.Qb) SB_WAIT_VMCNT(2);
-      else SB_WAIT_VMCNT(1);
-      sb_barrier_lds();
-    }
-  }
+  } while (FUSED && restart_solve);
 }
+
+template <int NJ, int WAVES>
+__global__ __launch_bounds__(64 * WAVES) void trsm_apply_kernel(TrsmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) double trsm_lds[];
+  trsm_body<NJ, WAVES, false>(g, blockIdx.x, trsm_lds, nullptr, nullptr);
+}
+
+template <int NJ, int WAVES, bool FUSED>
+static constexpr size_t trsm_lds_bytes() {
+  constexpr int J0 = FUSED ? 0 : TRSM_J0(NJ);
+  return ((size_t)(FUSED ? 0 : 16 * (8 * J0 * (J0 + 1) + 2)) + (NJ > J0 ? (size_t)32 * (16 * NJ + 2) : 0)) *
+             sizeof(double) + (size_t)WAVES * TRSM_TILE_FLOATS * sizeof(float) + 16;
+}
+
 template <int NJ, int WAVES>
 static int launch_trsm_nj_waves(hipStream_t s, const TrsmArgs& g) {
-  constexpr int J0 = TRSM_J0(NJ);
-  constexpr size_t lds = ((size_t)16 * (8 * J0 * (J0 + 1) + 2) + (NJ > J0 ? (size_t)32 * (16 * NJ + 2) : 0)) *
-                             sizeof(double) + (size_t)WAVES * TRSM_TILE_FLOATS * sizeof(float);
-  static bool attr_done = false;
-  if (lds > 64 * 1024 && !attr_done) {
+  constexpr size_t lds = trsm_lds_bytes<NJ, WAVES, false>();
+  static std::atomic<bool> attr_done{false};
+  if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)trsm_apply_kernel<NJ, WAVES>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(trsm LDS)");
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   LORACT_LAUNCH("trsm_apply", s, (trsm_apply_kernel<NJ, WAVES>),
                 dim3((unsigned)ceil_div64(g.m, 16 * WAVES)), dim3(64 * WAVES), lds, g);
   return LORACT_OK;
 }
+
+// ---------------------------------------------------------------------------------------------
+// Factorisation and triangular solve of round 1 in ONE launch: workgroup 0 factors the Gram
+// matrix (chol_reg_body, publishing), workgroups 1 .. solve their 128 rows of Y panel by panel
+// as the factor appears, so that the solve costs one panel step after the factorisation ends
+// instead of a launch of its own after it.  Workgroup 0 waits for nobody, and is dispatched
+// first, so the others' bounded waits cannot starve it.  The progress word must be zero when the
+// launch starts (an earlier kernel of the same call clears it).
+template <int SLOTS, int NJ>
+__global__ __launch_bounds__(CR_THREADS) void chol_trsm_fused_kernel(CholArgs c, int ptld, TrsmArgs g) {
+  extern __shared__ __attribute__((aligned(16))) double fused_lds[];
+  if (blockIdx.x == 0) chol_reg_body<SLOTS, true>(c, ptld, fused_lds);
+  else trsm_body<NJ, CR_THREADS / 64, true>(g, (int)blockIdx.x - 1, fused_lds, c.ready, c.status);
+}
+
 // Few rows: 64 per workgroup so that more CUs take part; many rows: 128, which halves the panel
 // traffic per row.
 template <int NJ>
@@ -1135,7 +1270,13 @@ __global__ __launch_bounds__(256) void ns_poly_square_kernel(NsPolyArgs g) {
 __global__ __launch_bounds__(256) void ns_poly_finish_kernel(NsPolyArgs g) {
   __shared__ double red[4];
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  if (!ns_poly_active(g, lane)) return;          // uniform over the grid: every wave sums the same shares
+  if (!ns_poly_active(g, lane)) {                // uniform over the grid: every wave sums the same shares
+    // Not prepared: say so in the share itself.  The factorisation kernel adds the shares of
+    // ||E||_F^2 in another order and may land on the other side of a threshold by a rounding;
+    // an infinite share makes it reject the series instead of reading a stale value.
+    if (threadIdx.x == 0) g.p4[blockIdx.x] = __builtin_huge_val();
+    return;
+  }
   const int nj = g.kp / 16;
   const int tile = blockIdx.x * 4 + wave;
   const bool on = tile < nj * nj;
@@ -1248,7 +1389,7 @@ static size_t gram_partial_bytes(int64_t m, int kp) {
 // ns_e2 needs 64 * gram_nblocks(kp) doubles.
 static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t m, int kp, int k,
                             double* part, double* G, double* G_copy = nullptr,
-                            bf16_t* ns_T = nullptr, double* ns_e2 = nullptr) {
+                            bf16_t* ns_T = nullptr, double* ns_e2 = nullptr, int32_t* clear_word = nullptr) {
   GramArgs g;
   g.Y = Y; g.ldy = ldy; g.m = m; g.kp = kp;
   g.nb64 = (kp + 63) / 64;
@@ -1258,7 +1399,7 @@ static int launch_gram_mfma(hipStream_t s, const float* Y, int64_t ldy, int64_t 
   const int chunks = (int)ceil_div64(m, g.rows_per_chunk);
   LORACT_LAUNCH("gram", s, gram_mfma_kernel, dim3(chunks, nblocks), dim3(256), 0, g);
   LORACT_LAUNCH("gram_reduce", s, gram_reduce_kernel, dim3(64, nblocks), dim3(256), 0,
-                (const double*)part, chunks, nblocks, kp, k, G, G_copy, ns_T, ns_e2);
+                (const double*)part, chunks, nblocks, kp, k, G, G_copy, ns_T, ns_e2, clear_word);
   return LORACT_OK;
 }
 
@@ -1285,6 +1426,40 @@ static int launch_chol_blocked(hipStream_t s, CholArgs a) {
   }
   LORACT_LAUNCH("chol", s, chol_blocked_kernel, dim3(1), dim3(512), chol_lds_bytes(a.kp), a);
   return LORACT_OK;
+}
+
+template <int SLOTS, int NJ>
+static int launch_chol_trsm_fused_nj(hipStream_t s, const CholArgs& c, const TrsmArgs& g) {
+  const int ptld = chol_reg_ptld(c.kp);
+  const size_t lds = std::max(chol_reg_lds_bytes(c.kp), trsm_lds_bytes<NJ, CR_THREADS / 64, true>());
+  static std::atomic<bool> attr_done{false};
+  if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
+    hipError_t e = hipFuncSetAttribute((const void*)chol_trsm_fused_kernel<SLOTS, NJ>,
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(fused factor-and-solve LDS)");
+    attr_done.store(true, std::memory_order_release);
+  }
+  const unsigned solvers = (unsigned)ceil_div64(g.m, 16 * (CR_THREADS / 64));
+  LORACT_LAUNCH("chol_trsm", s, (chol_trsm_fused_kernel<SLOTS, NJ>), dim3(1 + solvers), dim3(CR_THREADS), lds,
+                c, ptld, g);
+  return LORACT_OK;
+}
+
+// Round 1 in one launch when the register-resident factorisation applies (kp <= 256, unshifted
+// first attempt); c.ready must have been cleared by an earlier kernel.
+static bool chol_trsm_fusable(const CholArgs& c) {
+  return c.round == 1 && c.kp <= 256 && c.unshifted_thresh > 0.0 && c.G_backup && c.ready;
+}
+static int launch_chol_trsm_fused(hipStream_t s, CholArgs c, const TrsmArgs& g) {
+  c.tol = ((double)c.k * 5.9604644775390625e-08) * ((double)c.k * 5.9604644775390625e-08);
+  switch (c.kp / 16) {
+#define CF_CASE(N, S) case N: return launch_chol_trsm_fused_nj<S, N>(s, c, g);
+    CF_CASE(1, 5) CF_CASE(2, 5) CF_CASE(3, 5) CF_CASE(4, 5) CF_CASE(5, 5) CF_CASE(6, 5) CF_CASE(7, 5) CF_CASE(8, 5)
+    CF_CASE(9, 20) CF_CASE(10, 20) CF_CASE(11, 20) CF_CASE(12, 20) CF_CASE(13, 20) CF_CASE(14, 20)
+    CF_CASE(15, 20) CF_CASE(16, 20)
+#undef CF_CASE
+    default: return LORACT_ERR_UNSUPPORTED;
+  }
 }
 
 static int launch_trsm_apply(hipStream_t s, const TrsmArgs& g) {

@@ -1,18 +1,19 @@
 // Streaming bf16 kernels of the hot path: the passes over the activation X (tokens x hidden)
 // and the write of its reconstruction, on v_mfma_f32_32x32x16_bf16 with fp32 accumulation.
 //
-//   sketch       Y = X Bt^T          Algorithm 1 step 2 (Bt = sampled rows of X) and step 5
-//   project      V = Q^T X           Algorithm 1 step 8 (and step 5)
+//   sketch       Y = X Bt^T          Algorithm 1: the sketch (Bt = sampled rows of X) and the power rounds
+//   project      V = Q^T X           Algorithm 1: the projection onto the basis (and the power rounds)
 //   reconstruct  Xhat = U V          Section 3.1 Eq. (4)
 //
-// All three stage 64-deep K slabs through double-buffered LDS and give each of the 4 waves of
-// a workgroup a 64-row strip of accumulator tiles.  Operands whose contraction index is
-// contiguous in memory (rows of X in the sketch, rows of U in the reconstruction) are stored in
-// LDS as [row][K] and read back as 16-byte MFMA fragments.  Operands whose contraction index is
-// the row index of a row-major matrix (both operands of the projection, V in the
-// reconstruction) are stored "pair interleaved": LDS word [p][c] holds rows 2p and 2p+1 of
-// column c, so that four 4-byte LDS reads give a lane the 8 consecutive-K values of its column
-// with no register shuffling.
+// All three fill LDS with asynchronous global -> LDS copies, several slabs or tiles ahead, and
+// give each wave a strip of 32 x 32 accumulator tiles.  Operands whose contraction index is
+// contiguous in memory (both operands of the sketch, the rows of U in the reconstruction) lie in
+// LDS as [row][K] and are read back as 16-byte matrix-core fragments.  In the projection the
+// contraction index is the ROW index of both row-major operands: the slabs are copied as they
+// lie in memory and the fragments (8 consecutive rows of one column) come from the transposing
+// LDS read ds_read_b64_tr_b16.  Only the V operand of the reconstruction, which is staged once per
+// column block and then kept in registers, is stored "pair interleaved" (LDS word [p][c] holds
+// rows 2p and 2p+1 of column c) and read with four 4-byte LDS reads per fragment.
 //
 // Fast-path requirements (checked by the host, which otherwise falls back to gemm_bf16.h):
 // 16-byte aligned base pointers and leading dimensions that are multiples of 8 elements.
@@ -368,13 +369,13 @@ static inline bool sb_aligned(const void* p, int64_t ld) {
 template <int NT, int WM>
 static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const char* name) {
   constexpr int STAGES = WM == 4 ? 2 : (NT == 4 ? 3 : 4);
-  static bool attr_done = false;
+  static std::atomic<bool> attr_done{false};
   const size_t lds = sketch_lds_bytes(NT, WM);
-  if (lds > 64 * 1024 && !attr_done) {
+  if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, STAGES, WM>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(sketch LDS)");
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, STAGES, WM>), grid, dim3(128 * WM), lds, g);
   return LORACT_OK;
@@ -757,13 +758,13 @@ static size_t project_part_floats(int64_t m, int64_t n, int l) {
 
 template <int NTQ, int NTX, int STAGES, int WN>
 static int launch_project_shape(hipStream_t s, const ProjectArgs& g, const char* name) {
-  static bool attr_done = false;
+  static std::atomic<bool> attr_done{false};
   const size_t lds = project_lds_bytes(NTQ, NTX, STAGES, WN);
-  if (lds > 64 * 1024 && !attr_done) {
+  if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES, WN>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(project LDS)");
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES, WN>), dim3((unsigned)g.wgs), dim3(128 * WN), lds, g);
   return LORACT_OK;
@@ -1034,13 +1035,13 @@ static size_t reconstruct_lds_bytes(int nks) {
 template <int NKS>
 static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) {
   constexpr bool WIDE = NKS > 8 && NKS <= 16;    // beyond 16 K steps the V fragments leave no registers
-  static bool attr_done = false;
+  static std::atomic<bool> attr_done{false};
   const size_t lds = reconstruct_lds_bytes(NKS);
-  if (lds > 64 * 1024 && !attr_done) {
+  if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)reconstruct_mfma_kernel<NKS, WIDE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(reconstruct LDS)");
-    attr_done = true;
+    attr_done.store(true, std::memory_order_release);
   }
   LORACT_LAUNCH("reconstruct", s, (reconstruct_mfma_kernel<NKS, WIDE>), grid, dim3(256), lds, g);
   return LORACT_OK;
@@ -1129,12 +1130,12 @@ static int launch_lora_vtt_rp(hipStream_t s, const bf16_t* V, const float* Tspli
                               float scale, float* dA) {
   const int rp = 16 * RP16;
   const size_t lds = ((size_t)k * rp + (size_t)8 * 32 * (rp + 1)) * sizeof(float);
-  static size_t attr_bytes = 64 * 1024;
-  if (lds > attr_bytes) {
+  static std::atomic<size_t> attr_bytes{64 * 1024};
+  if (lds > attr_bytes.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)lora_vtt_kernel<RP16>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(lora_vtt LDS)");
-    attr_bytes = lds;
+    attr_bytes.store(lds, std::memory_order_release);
   }
   LORACT_LAUNCH("lora_vtt", s, lora_vtt_kernel<RP16>, dim3((unsigned)ceil_div64(n, 32)), dim3(256), lds, V,
                 Tsplit, k, n, r, scale, dA);

@@ -40,12 +40,25 @@ def test_version_and_strerror():
 @pytest.mark.parametrize("m,l", [(1, 1), (10, 3), (17, 17), (1000, 37), (8192, 128), (65536, 256),
                                   (12608, 64)])
 def test_sample_indices_agree_with_oracle_definition(m, l):
-    # Both sides implement Algorithm 1 step 1 independently (splitmix64 + Floyd, sorted).
+    # Both sides implement the row sampling of Algorithm 1 independently (splitmix64 + Floyd, sorted).
     lib = _lib.load()
     buf = (ctypes.c_int32 * l)()
     for seed in (0, 1, 2, 12345, 2 ** 63 + 11, 2 ** 64 - 1):
         assert lib.loract_sample_indices(m, l, seed, buf) == 0
         assert list(buf) == orc.sample_indices(m, l, seed).tolist()
+
+
+def test_sample_indices_reproduce_the_hand_derived_vectors():
+    # the library against the hand derivations themselves (tests/golden), not only against the
+    # oracle: the vectors include draws that land on an id already chosen
+    lib = _lib.load()
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden", "sample_indices_vectors.txt")
+    rows = [[int(t) for t in ln.split()] for ln in open(path) if ln.strip() and not ln.startswith("#")]
+    assert len(rows) >= 3
+    for m, l, seed, *expected in rows:
+        buf = (ctypes.c_int32 * l)()
+        assert lib.loract_sample_indices(m, l, seed, buf) == 0
+        assert list(buf) == expected
 
 
 def test_sample_indices_rejects_bad_arguments():

@@ -58,7 +58,7 @@ def test_sample_indices_distinct_sorted_in_range(m, l):
 
 
 def test_sample_indices_uniform_chi_square():
-    # Algorithm 1 step 1 / Theorem 4.3: *uniform* row sampling.  Every row of m = 20 should be
+    # Row sampling of Algorithm 1 / Theorem 4.3: *uniform* row sampling.  Every row of m = 20 should be
     # picked with probability l/m = 0.25; chi-square over 4000 seeds, 19 dof, 99.9% quantile 43.8.
     m, l, trials = 20, 5, 4000
     counts = np.zeros(m)
@@ -109,7 +109,7 @@ def test_decompose_shapes_orthonormal_and_projection(m, n, k, t):
         u, v = orc.decompose(a, k, t=t, seed=seed)
         assert u.shape == (m, k) and v.shape == (k, n)               # Section 3.1: U m x k, V k x n
         assert orc.orthogonality_defect(u) <= 1e-12
-        assert np.allclose(v, u.T @ a, atol=1e-12 * np.abs(a).max() * m)  # step 8: V = Q^T A
+        assert np.allclose(v, u.T @ a, atol=1e-12 * np.abs(a).max() * m)  # V = Q^T A
 
 
 @pytest.mark.parametrize("m,n,k", [(64, 24, 4), (64, 24, 12), (30, 50, 9)])
@@ -182,7 +182,7 @@ def test_closed_form_on_scaled_orthonormal_rows():
 
 
 def test_power_iterations_approach_truncated_svd():
-    # Algorithm 1 steps 3-6: with a spectral gap the range of (A A^T)^t A Omega converges to
+    # Power rounds of Algorithm 1: with a spectral gap the range of (A A^T)^t A Omega converges to
     # the leading left singular subspace, so the error tends to the Eckart-Young optimum.
     rng = np.random.default_rng(21)
     s = np.concatenate([np.linspace(10, 5, 6), np.linspace(0.5, 0.1, 18)])
@@ -250,6 +250,32 @@ def test_prenorm_backward_matches_finite_difference():
         fp = np.sum(grad_a * orc.prenorm_forward(x + e, gamma)[0])
         fm = np.sum(grad_a * orc.prenorm_forward(x - e, gamma)[0])
         assert abs((fp - fm) / (2 * h) - dx[i, j]) <= 1e-7
+
+
+def test_prenorm_forward_closed_forms():
+    # Eq. (7) pinned by what it must produce, not by retyping it:
+    # (a) gamma = 1, eps = 0: every row of A has unit root-mean-square;
+    rng = np.random.default_rng(12)
+    m, n = 7, 24
+    x = rng.standard_normal((m, n)) * rng.uniform(0.1, 30.0, size=(m, 1))
+    a, rms = orc.prenorm_forward(x, np.ones(n))
+    assert np.allclose(np.sum(a * a, axis=1), n, rtol=1e-13)
+    # (b) the RMS vector times A / gamma gives X back (what the backward pass relies on, Eq. 8);
+    gamma = rng.uniform(0.5, 2.0, size=n)
+    a, rms = orc.prenorm_forward(x, gamma)
+    assert np.allclose(a / gamma[None, :] * rms[:, None], x, rtol=1e-13)
+    # (c) a row of +-c has RMS c and normalises to +-gamma; scaling a row leaves A unchanged;
+    signs = np.where(rng.random(n) < 0.5, -1.0, 1.0)
+    a1, r1 = orc.prenorm_forward(3.5 * signs[None, :], gamma)
+    assert r1[0] == pytest.approx(3.5, rel=1e-15) and np.allclose(a1[0], signs * gamma, rtol=1e-15)
+    a2, r2 = orc.prenorm_forward(17.0 * x, gamma)
+    assert np.allclose(a2, a, rtol=1e-13) and np.allclose(r2, 17.0 * rms, rtol=1e-13)
+    # (d) a worked row: x = (3, 4, 0, 0): mean square 25/4, RMS 5/2, A = (6/5, 8/5, 0, 0) gamma
+    a3, r3 = orc.prenorm_forward(np.array([[3.0, 4.0, 0.0, 0.0]]), np.array([1.0, 2.0, 1.0, 1.0]))
+    assert r3[0] == 2.5 and np.allclose(a3[0], [1.2, 3.2, 0.0, 0.0], rtol=1e-15)
+    # (e) eps enters under the root: an all-zero row stays finite and maps to zero
+    a4, r4 = orc.prenorm_forward(np.zeros((1, 4)), np.ones(4), eps=1e-6)
+    assert r4[0] == pytest.approx(1e-3) and np.all(a4 == 0.0)
 
 
 # ----------------------------------------------------------------------------- RSVD comparator
@@ -387,7 +413,7 @@ def test_planted_mistakes_violate_the_pins():
     def correct(a, k, seed):
         return orc.decompose(a, k, seed=seed)
 
-    def no_final_qr(a, k, seed):              # drops step 7: U = normalised Y instead of Q
+    def no_final_qr(a, k, seed):              # drops the final QR: U = normalised Y instead of Q
         idx = orc.sample_indices(a.shape[0], k, seed)
         y = a @ a[idx, :].T
         u = y / np.linalg.norm(y, axis=0, keepdims=True)
