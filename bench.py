@@ -153,7 +153,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "coherent", "c5stream"])
+    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "c5", "coherent", "c5stream"])
     ap.add_argument("--layers", type=int, default=2,
                     help="c5stream only: decoder layers to stream (7 sites each; the full config is 32)")
     ap.add_argument("--streams", type=int, default=3,
@@ -163,6 +163,10 @@ def main() -> int:
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run 5 plain device copies of X (2*|X| bytes of known traffic each) so "
                          "that rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings can be scaled")
+    ap.add_argument("--profile-pass", action="store_true",
+                    help="run only warm single-stream steps (no cold-cache flush, no pipelined section, no "
+                         "comparator, no event profiling) and print a short JSON line: the run to put under "
+                         "rocprofv3 --kernel-trace / --pmc, so that every kernel average is one role's warm figure")
     ap.add_argument("--traffic-json", default=os.path.join(ROOT, "profiles", "traffic.json"))
     args = ap.parse_args()
     if args.gpus != 1:
@@ -231,6 +235,17 @@ def main() -> int:
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     x_bytes = m * n * b
+
+    if args.profile_pass:
+        if args.pmc_calibration:
+            scratch = torch.empty_like(x)
+            for _ in range(5):
+                scratch.copy_(x)
+            torch.cuda.synchronize()
+        print(json.dumps({"profile_pass": True, "workload": args.workload, "steps": args.steps,
+                          "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+                          "launch_order": "compress, reconstruct, lora_grad per step, one stream"}))
+        return 0
 
     # per-phase times (separate region, events on the stream the library launches on)
     def timed(fn):

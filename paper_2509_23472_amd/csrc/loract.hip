@@ -288,11 +288,12 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
     LORACT_TRY(launch_chol_blocked(c.s, ch));
     LORACT_TRY(launch_trsm_apply(c.s, t));
   }
-  ch.ready = nullptr;
   // round 2: either Q = Q1 (I - E/2) when E = Q1^T Q1 - I is small, or a second Cholesky QR
   double* ns_e2 = ws_ptr<double>(c, c.pl.off_flag) + 8;      // after the flag word
-  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr, ns_e2));
   ch.round = 2;
+  const bool fused2 = chol_trsm_fusable(ch);
+  LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr, ns_e2,
+                              fused2 ? ch.ready : nullptr));
   ch.ns_e2 = ns_e2; ch.ns_e2_count = 64 * gram_nblocks(kp); ch.ns_flag = ns_flag;
   ch.ns_tol = ns_ok ? 0.015 : 0.0;
   // Tall matrices: when the first-order finish does not reach, a degree-4 correction is prepared
@@ -306,10 +307,15 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
     ch.poly_p4 = np.p4; ch.poly_count = ns_poly_blocks(kp); ch.poly_hi_tol = np.hi_tol; ch.poly_b4_tol = 0.2;
   }
   ch.ns_exact_tol = 1e-6;             // Q1 is then orthonormal to 1e-6 already: nothing for round 2 to do
-  LORACT_TRY(launch_chol_blocked(c.s, ch));
   t.Y = tmp; t.Q = Q; t.ldq = l; t.out_ek = q_ek; t.out_cols = l; t.Qb = Qb; t.ldqb = l;
-  t.skip_flag = ns_flag;
-  LORACT_TRY(launch_trsm_apply(c.s, t));
+  if (fused2) {
+    t.skip_flag = nullptr;            // every workgroup of the fused launch takes the decision itself
+    LORACT_TRY(launch_chol_trsm_fused(c.s, ch, t));
+  } else {
+    LORACT_TRY(launch_chol_blocked(c.s, ch));
+    t.skip_flag = ns_flag;
+    LORACT_TRY(launch_trsm_apply(c.s, t));
+  }
   if (ns_ok) {
     // Q = Q1 + Q1b T^T (T symmetric) for flag 1, Q = Q1 for flag 2, nothing for flag 0: the
     // product kernel of the sketch with the finish fused into its epilogue
@@ -600,7 +606,7 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
     ProjectArgs pa;
     pa.Q = (const bf16_t*)U_dev; pa.ldq = k; pa.X = Gsplit; pa.ldx = 2 * rp; pa.m = m; pa.n = 2 * rp;
     pa.l = k; pa.V = ws + lp.off_tsplit; pa.out_ek = EK_F32; pa.part = (float*)(ws + lp.off_ppart);
-    LORACT_TRY(launch_project_mfma(s, pa, "lora_utg"));
+    LORACT_TRY(launch_project_mfma(s, pa, "lora_utg", PJ_LORA_UTG));
     // dA = scale * V^T (T_hi + T_lo)
     return launch_lora_vtt(s, (const bf16_t*)V_dev, (const float*)(ws + lp.off_tsplit), (int)k, n,
                            (int)r_lora, rp, scale, dA_dev);

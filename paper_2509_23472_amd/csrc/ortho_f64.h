@@ -281,7 +281,7 @@ __device__ inline int cf_poll(const int32_t* ready) {
 // Round 2 decision, taken by the whole workgroup before any factorisation work: E = G - I has been
 // measured by gram_reduce_kernel (||E||_F^2 in pieces, T = -E/2 already written).  Returns true,
 // with *ns_flag set, when no second factorisation is needed; misc is an LDS scratch of 4 doubles.
-__device__ inline bool chol_round2_exit(const CholArgs& g, double* misc) {
+__device__ inline bool chol_round2_exit(const CholArgs& g, double* misc, const bool write_flag = true) {
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   // wave 0 adds the shares (lane i takes shares i, i + 64, ...; butterfly sum, so every lane
   // ends with the same value) and hands the total to the other waves through LDS
@@ -303,11 +303,11 @@ __device__ inline bool chol_round2_exit(const CholArgs& g, double* misc) {
   __syncthreads();
   const double tot = misc[1];
   if (tot <= g.ns_exact_tol * g.ns_exact_tol) {     // Q1 is orthonormal as it stands
-    if (t == 0) *g.ns_flag = 2;
+    if (t == 0 && write_flag) *g.ns_flag = 2;
     return true;
   }
   if (g.ns_tol > 0.0 && tot <= g.ns_tol * g.ns_tol) {       // comparisons are false for NaN
-    if (t == 0) *g.ns_flag = 1;
+    if (t == 0 && write_flag) *g.ns_flag = 1;
     return true;
   }
   if (g.ns_tol > 0.0 && g.poly_count > 0 && tot <= g.poly_hi_tol * g.poly_hi_tol) {
@@ -323,11 +323,11 @@ __device__ inline bool chol_round2_exit(const CholArgs& g, double* misc) {
     __syncthreads();
     const double b4 = sqrt(sqrt(sqrt(misc[2])));
     if (b4 <= g.poly_b4_tol) {
-      if (t == 0) *g.ns_flag = 1;
+      if (t == 0 && write_flag) *g.ns_flag = 1;
       return true;
     }
   }
-  if (t == 0) *g.ns_flag = 0;
+  if (t == 0 && write_flag) *g.ns_flag = 0;
   return false;
 }
 
@@ -609,7 +609,8 @@ __device__ inline void chol_reg_body(const CholArgs& g, const int ptld, double* 
   const int pm = 4 * (lc & 3) + (lc >> 2);   // accumulator row of logical row lc, and back
   if (t == 0) { deficient = 0; restart = 0; }
   __syncthreads();
-  if (g.round == 2 && g.ns_flag && chol_round2_exit(g, misc)) return;
+  // (in the fused launch every workgroup has taken the round-2 decision before it got here)
+  if (!PUB && g.round == 2 && g.ns_flag && chol_round2_exit(g, misc)) return;
 
   // ---- block ownership: worker w holds blocks e = s * 7 + w of the row-major upper triangle
   // without block (0, 0), which wave 0 reads itself
@@ -1193,6 +1194,15 @@ static int launch_trsm_nj_waves(hipStream_t s, const TrsmArgs& g) {
 template <int SLOTS, int NJ>
 __global__ __launch_bounds__(CR_THREADS) void chol_trsm_fused_kernel(CholArgs c, int ptld, TrsmArgs g) {
   extern __shared__ __attribute__((aligned(16))) double fused_lds[];
+  // Round 2: whether Q1 needs a second factorisation at all is decided from the shares of
+  // ||E||_F^2 that the Gram reduction left -- by every workgroup for itself, with the same
+  // arithmetic in the same order, so that on the usual exits (Newton-Schulz finish, or Q1 accepted
+  // as it is) the whole launch ends after one look at those few hundred numbers and nobody waits
+  // for anybody.  Workgroup 0 records the decision in *ns_flag.
+  if (c.round == 2 && c.ns_flag) {
+    if (chol_round2_exit(c, fused_lds, blockIdx.x == 0)) return;
+    __syncthreads();
+  }
   if (blockIdx.x == 0) chol_reg_body<SLOTS, true>(c, ptld, fused_lds);
   else trsm_body<NJ, CR_THREADS / 64, true>(g, (int)blockIdx.x - 1, fused_lds, c.ready, c.status);
 }
@@ -1445,10 +1455,11 @@ static int launch_chol_trsm_fused_nj(hipStream_t s, const CholArgs& c, const Trs
   return LORACT_OK;
 }
 
-// Round 1 in one launch when the register-resident factorisation applies (kp <= 256, unshifted
-// first attempt); c.ready must have been cleared by an earlier kernel.
+// One launch per round when the register-resident factorisation applies (kp <= 256; round 1:
+// unshifted first attempt); c.ready must have been cleared by an earlier kernel.
 static bool chol_trsm_fusable(const CholArgs& c) {
-  return c.round == 1 && c.kp <= 256 && c.unshifted_thresh > 0.0 && c.G_backup && c.ready;
+  if (c.kp > 256 || !c.ready) return false;
+  return c.round == 2 || (c.unshifted_thresh > 0.0 && c.G_backup);
 }
 static int launch_chol_trsm_fused(hipStream_t s, CholArgs c, const TrsmArgs& g) {
   c.tol = ((double)c.k * 5.9604644775390625e-08) * ((double)c.k * 5.9604644775390625e-08);

@@ -141,7 +141,11 @@ struct SketchArgs {
 
 // WM = 64-row wave groups per workgroup: 2 (4 waves, 128 rows) or 4 (8 waves, 256 rows; halves the
 // re-reads of Bt per row of X, for matrices tall enough to fill the CUs with 256-row tiles).
-template <int NT, int STAGES, int WM>
+// ROLE only names the use in the kernel's symbol, so that a profile tells the uses apart:
+// 0 the sketch of Algorithm 1, 1 the product dY B_lora^T of the LoRA gradient, 2 the finish of
+// the orthonormalisation.  The code is the same.
+enum { SK_SKETCH = 0, SK_LORA_DYB = 1, SK_NS_CORRECT = 2 };
+template <int NT, int STAGES, int WM, int ROLE>
 __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   constexpr int BM = 64 * WM, BN = 64 * NT;
   constexpr int NB = 4 * NT / WM;       // Bt copy instructions per wave per slab
@@ -360,24 +364,24 @@ static inline int sketch_splits_for(int64_t m, int64_t n, int kp) {
 
 // A matrix of this many bytes does not survive in the 256 MB memory-side cache between two
 // passes, so caching its lines only evicts the small operands that are re-read.
-static inline int sb_streams_past_cache(int64_t bytes) { return bytes >= ((int64_t)192 << 20); }
+static inline int sb_streams_past_cache(int64_t bytes, int limit_mb = 192) { return bytes >= ((int64_t)limit_mb << 20); }
 
 static inline bool sb_aligned(const void* p, int64_t ld) {
   return (((uintptr_t)p) % 16 == 0) && (ld % 8 == 0);
 }
 
-template <int NT, int WM>
+template <int NT, int WM, int ROLE>
 static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const char* name) {
   constexpr int STAGES = WM == 4 ? 2 : (NT == 4 ? 3 : 4);
   static std::atomic<bool> attr_done{false};
   const size_t lds = sketch_lds_bytes(NT, WM);
   if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, STAGES, WM>,
+    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, STAGES, WM, ROLE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(sketch LDS)");
     attr_done.store(true, std::memory_order_release);
   }
-  LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, STAGES, WM>), grid, dim3(128 * WM), lds, g);
+  LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, STAGES, WM, ROLE>), grid, dim3(128 * WM), lds, g);
   return LORACT_OK;
 }
 
@@ -400,11 +404,18 @@ static int launch_sketch_mfma(hipStream_t s, SketchArgs g, const char* name = "s
   if (grid.y > 65535) return LORACT_ERR_UNSUPPORTED;
   if (split_out && g.splits == 1) g.Y = g.part;     // single split: Y itself is the "partial"
   int rc;
-  switch (nt) {
-    case 1: rc = launch_sketch_nt<1, 2>(s, g, grid, name); break;
-    case 2: rc = launch_sketch_nt<2, 2>(s, g, grid, name); break;
-    default: rc = wm == 4 ? launch_sketch_nt<4, 4>(s, g, grid, name) : launch_sketch_nt<4, 2>(s, g, grid, name); break;
+  const int role = g.fin_q ? SK_NS_CORRECT : (split_out ? SK_LORA_DYB : SK_SKETCH);
+#define SK_LAUNCH(ROLE)                                                                                   \
+  switch (nt) {                                                                                           \
+    case 1: rc = launch_sketch_nt<1, 2, ROLE>(s, g, grid, name); break;                                   \
+    case 2: rc = launch_sketch_nt<2, 2, ROLE>(s, g, grid, name); break;                                   \
+    default: rc = wm == 4 ? launch_sketch_nt<4, 4, ROLE>(s, g, grid, name)                                \
+                          : launch_sketch_nt<4, 2, ROLE>(s, g, grid, name); break;                        \
   }
+  if (role == SK_NS_CORRECT) { SK_LAUNCH(SK_NS_CORRECT) }
+  else if (role == SK_LORA_DYB && nt == 1) rc = launch_sketch_nt<1, 2, SK_LORA_DYB>(s, g, grid, name);
+  else { SK_LAUNCH(SK_SKETCH) }
+#undef SK_LAUNCH
   if (rc != LORACT_OK) return rc;
   if (split_out)
     return launch_sum_partials(s, g.part, g.splits, g.m, g.kp, g.kp, split_out, 2 * g.kp, EK_BF16_SPLIT);
@@ -487,7 +498,10 @@ __device__ inline s16x4 sb_read_tr(const unsigned char* lds_ptr) {
 
 // Output tile (64 NTQ) x (32 NTX WN), waves 2 x WN, each with NTQ x NTX matrix-core tiles.
 // WN = 4 (8 waves, 256 columns of X for NTX = 2) halves the re-reads of Q per byte of X.
-template <int NTQ, int NTX, int STAGES, int WN>
+// ROLE only names the use in the kernel's symbol: 0 the projection V = Q^T X, 1 the product
+// U^T [G_hi | G_lo] of the LoRA gradient.
+enum { PJ_PROJECT = 0, PJ_LORA_UTG = 1 };
+template <int NTQ, int NTX, int STAGES, int WN, int ROLE>
 __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
   constexpr int NW = 2 * WN;                       // waves
   constexpr int BMQ = 64 * NTQ, BNX = 32 * NTX * WN;
@@ -756,25 +770,29 @@ static size_t project_part_floats(int64_t m, int64_t n, int l) {
   return (size_t)g.wgs * g.segs_max * g.bmq * g.bnx;
 }
 
-template <int NTQ, int NTX, int STAGES, int WN>
+template <int NTQ, int NTX, int STAGES, int WN, int ROLE>
 static int launch_project_shape(hipStream_t s, const ProjectArgs& g, const char* name) {
   static std::atomic<bool> attr_done{false};
   const size_t lds = project_lds_bytes(NTQ, NTX, STAGES, WN);
   if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES, WN>,
+    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES, WN, ROLE>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(project LDS)");
     attr_done.store(true, std::memory_order_release);
   }
-  LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES, WN>), dim3((unsigned)g.wgs), dim3(128 * WN), lds, g);
+  LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES, WN, ROLE>), dim3((unsigned)g.wgs), dim3(128 * WN), lds, g);
   return LORACT_OK;
 }
 
-static int launch_project_main(hipStream_t s, const ProjectArgs& g, const char* name) {
-  if (g.l <= 64) return launch_project_shape<1, 2, 2, 2>(s, g, name);
-  if (g.l <= 128) return launch_project_shape<2, 2, 2, 2>(s, g, name);
-  if (g.m < 32768) return launch_project_shape<4, 2, 3, 2>(s, g, name);
-  return launch_project_shape<4, 2, 2, 4>(s, g, name);
+template <int ROLE>
+static int launch_project_role(hipStream_t s, const ProjectArgs& g, const char* name) {
+  if (g.l <= 64) return launch_project_shape<1, 2, 2, 2, ROLE>(s, g, name);
+  if (g.l <= 128) return launch_project_shape<2, 2, 2, 2, ROLE>(s, g, name);
+  if (g.m < 32768) return launch_project_shape<4, 2, 3, 2, ROLE>(s, g, name);
+  return launch_project_shape<4, 2, 2, 4, ROLE>(s, g, name);
+}
+static int launch_project_main(hipStream_t s, const ProjectArgs& g, const char* name, int role) {
+  return role == PJ_LORA_UTG ? launch_project_role<PJ_LORA_UTG>(s, g, name) : launch_project_role<PJ_PROJECT>(s, g, name);
 }
 static int launch_project_sum(hipStream_t s, const ProjectArgs& g) {
   const int64_t tiles = (int64_t)g.col_blocks * ceil_div64(g.l, g.bmq);
@@ -791,10 +809,13 @@ static int launch_project_sum(hipStream_t s, const ProjectArgs& g) {
 
 // Requires 16-byte aligned rows of Q, X and V (l, ldq, ldx, n multiples of 8; checked by the
 // caller); part: project_part_floats(m, n, l) floats.
-static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = "project") {
+static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = "project", int role = PJ_PROJECT) {
   project_plan(&g);
-  g.stream_x = sb_streams_past_cache(g.m * g.n * 2);
-  int rc = launch_project_main(s, g, name);
+  // (the projection is the last reader of X inside a compress: above 128 MB its lines only push the
+  // basis, which every column block re-reads, out of L2 -- measured at 8192 x 11008: twice the
+  // algorithmic bytes fetched, 108 -> 103 us)
+  g.stream_x = sb_streams_past_cache(g.m * g.n * 2, 128);
+  int rc = launch_project_main(s, g, name, role);
   if (rc != LORACT_OK) return rc;
   return launch_project_sum(s, g);
 }

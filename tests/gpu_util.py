@@ -128,13 +128,16 @@ def check_compress_parity(w: synth.Workload, u_gpu: torch.Tensor, v_gpu: torch.T
     assert res["ortho"] <= res["ortho_tol"], res
     # approximation quality: a basis-independent scalar that is far below the parity tolerance
     bf16_factors = u_gpu.dtype == torch.bfloat16
+    # (bf16 inputs: the basis enters the projection rounded to bf16 whatever the factor type is)
     storage_noise = 0.0
-    if bf16_factors:
+    if w.dtype == "bf16":
         ub = synth.round_to_bf16(uo.astype(np.float32)).astype(np.float64)
-        vb = synth.round_to_bf16((ub.T @ w.x.astype(np.float64)).astype(np.float32)).astype(np.float64)
-        ub_r = ub if rows is None else ub[rows]
-        storage_noise = abs(orc.rel_fro(ub_r @ vb, x) - res["quality_oracle"])
-        del ub, vb, ub_r
+        vb = ub.T @ w.x.astype(np.float64)
+        if bf16_factors:
+            vb = synth.round_to_bf16(vb.astype(np.float32)).astype(np.float64)
+        u_used = ub if bf16_factors else uo
+        storage_noise = abs(orc.rel_fro((u_used if rows is None else u_used[rows]) @ vb, x) - res["quality_oracle"])
+        del ub, vb, u_used
     res["quality_tol"] = 0.1 * res["quality_oracle"] + 1.5 * storage_noise + 1e-6
     assert abs(res["quality_gpu"] - res["quality_oracle"]) <= res["quality_tol"], res
     if local:
