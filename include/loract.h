@@ -46,6 +46,7 @@ typedef enum { LORACT_F32 = 0, LORACT_BF16 = 1 } loract_dtype;
 
 /* Largest number of sketch columns (k, or k + oversampling for RSVD) the kernels accept. */
 #define LORACT_MAX_RANK 320
+#define LORACT_STATIC_SCRATCH_BYTES (16u << 20)   /* scratch built into the library, see loract_lora_grad_static */
 
 /* Bits of the device status word written by loract_compress / loract_rsvd. */
 #define LORACT_STATUS_RANK_DEFICIENT 1   /* a direction of the sketch was numerically dependent on
@@ -134,6 +135,28 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
                      int32_t factor_dtype, const void* dY_dev, int64_t n_out,
                      const void* Blora_dev, int32_t r_lora, int32_t grad_dtype, float scale,
                      float* dA_dev, void* ws_dev, size_t ws_bytes, void* stream);
+
+/*
+ * loract_lora_grad for callers that cannot allocate or hand over device memory: code under HIP
+ * graph capture, tight serving or training loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and result (bit for bit) as loract_lora_grad, without the workspace: the
+ * scratch is a buffer of LORACT_STATIC_SCRATCH_BYTES (16 MiB) built into the library's device
+ * image, one copy per GPU, held until the process ends.  The call allocates nothing: no hipMalloc,
+ * hipFree or allocating library routine is reached.
+ * Limit: shapes whose loract_lora_grad_workspace_bytes exceeds LORACT_STATIC_SCRATCH_BYTES are
+ * rejected with LORACT_ERR_WORKSPACE_TOO_SMALL (loract_last_hip_error names both sizes) before
+ * anything is enqueued; 8192 x 4096, rank 128, LoRA rank 16 needs 8 MiB.
+ * All calls on one GPU share that GPU's buffer, which keeps the previous call's contents (no kernel
+ * of the gradient relies on them): calls that overlap on one GPU -- from two streams or two
+ * threads -- race; serialise them on one stream.  The first call on a device looks up the
+ * buffer's address (no allocation, but not a stream operation: make one call before capturing).
+ * loract_static_scratch_bytes returns the built-in size.
+ */
+size_t loract_static_scratch_bytes(void);
+int loract_lora_grad_static(const void* U_dev, const void* V_dev, int64_t m, int64_t n, int32_t k,
+                            int32_t factor_dtype, const void* dY_dev, int64_t n_out,
+                            const void* Blora_dev, int32_t r_lora, int32_t grad_dtype, float scale,
+                            float* dA_dev, void* stream);
 
 /*
  * The comparator of Section 3.2: randomized SVD with a Gaussian test matrix Omega (n x l),

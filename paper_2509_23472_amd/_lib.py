@@ -38,6 +38,9 @@ SIGNATURES = {
     "loract_lora_grad_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, _i64, _i32, _P(_sz)]),
     "loract_lora_grad": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i32, _i32,
                                         ctypes.c_float, _vp, _vp, _sz, _vp]),
+    "loract_static_scratch_bytes": (_sz, []),
+    "loract_lora_grad_static": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i32, _i32,
+                                               ctypes.c_float, _vp, _vp]),
     "loract_rsvd": (ctypes.c_int, [_vp, _P(LoractParams), _vp, _vp, _vp, _vp, _sz, _vp, _vp]),
     "loract_gaussian_omega_t": (ctypes.c_int, [_vp, _i32, _i64, _i32, _u64, _vp]),
     "loract_prenorm_forward": (ctypes.c_int, [_vp, _i64, _i64, _i64, _i32, _vp, ctypes.c_float, _vp, _i64,

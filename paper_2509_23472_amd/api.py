@@ -185,6 +185,34 @@ def loract_lora_grad(u: torch.Tensor, v: torch.Tensor, dy: torch.Tensor, b_lora:
     return out
 
 
+def loract_lora_grad_static(u: torch.Tensor, v: torch.Tensor, dy: torch.Tensor, b_lora: torch.Tensor,
+                            out: torch.Tensor, scale: float = 1.0) -> torch.Tensor:
+    """loract_lora_grad on the scratch buffer built into the library: nothing is allocated, here or
+    in the library, so `out` (n x r float32) must be given.  Shapes that need more than
+    loract_static_scratch_bytes() of scratch raise LoractError."""
+    _require_cuda(u, v, dy, b_lora, out)
+    m, k = u.shape
+    n = v.shape[1]
+    if v.shape[0] != k or dy.shape[0] != m or b_lora.shape[1] != dy.shape[1] or u.dtype != v.dtype \
+            or dy.dtype != b_lora.dtype:
+        raise ValueError("shape or dtype mismatch")
+    for tns in (u, v, dy, b_lora, out):
+        if not tns.is_contiguous():
+            raise ValueError("operands must be contiguous")
+    n_out, r = dy.shape[1], b_lora.shape[0]
+    if out.shape != (n, r) or out.dtype != torch.float32:
+        raise ValueError("out must be a contiguous n x r float32 tensor")
+    _check(_lib.load().loract_lora_grad_static(
+        u.data_ptr(), v.data_ptr(), m, n, k, _dtype_code(u.dtype), dy.data_ptr(), n_out,
+        b_lora.data_ptr(), r, _dtype_code(dy.dtype), float(scale), out.data_ptr(), _stream_ptr()),
+        "loract_lora_grad_static")
+    return out
+
+
+def loract_static_scratch_bytes() -> int:
+    return int(_lib.load().loract_static_scratch_bytes())
+
+
 def loract_gaussian_omega_t(l: int, n: int, dtype: torch.dtype, seed: int,
                             device: Optional[torch.device] = None) -> torch.Tensor:
     """The comparator's Gaussian test matrix, stored transposed (l x n), generated on the GPU."""

@@ -409,6 +409,37 @@ static int power_iterations(const Ctx& c, void* Y, void* tmp) {
 }
 
 // ---------------------------------------------------------------------------------------------
+// Scratch memory owned by the library, for the one entry point that must not allocate
+// (loract_lora_grad_static).  The array's name is only a host-side stand-in for the symbol: its
+// device address is looked up once per device with hipGetSymbolAddress and that pointer is what
+// kernels and copies receive.  Every GPU that loads the library holds its own copy until the
+// process ends.
+
+static __device__ __align__(256) unsigned char scratch[LORACT_STATIC_SCRATCH_BYTES];
+
+#define LORACT_MAX_DEVICES 64
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[LORACT_MAX_DEVICES];
+
+// Device address of this GPU's `scratch` (looked up on the first call on each device).
+static int static_scratch_ptr(void** out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+  if (dev < 0 || dev >= LORACT_MAX_DEVICES) return LORACT_ERR_UNSUPPORTED;
+  std::lock_guard<std::mutex> lock(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(scratch));
+    if (e != hipSuccess) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+    if (!ptr) return LORACT_ERR_HIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return LORACT_OK;
+}
+
+// ---------------------------------------------------------------------------------------------
 // C ABI.
 
 extern "C" {
@@ -625,6 +656,28 @@ int loract_lora_grad(const void* U_dev, const void* V_dev, int64_t m, int64_t n,
   // dA = V^T T * scale  (n x r)
   return launch_gemm_f64("lora_vtt_generic", s, V_dev, n, 0, f_ek, T, r_lora, 0, EK_F32, nullptr, n, r_lora,
                          k, (double)scale, dA_dev, r_lora, EK_F32, 1, nullptr);
+}
+
+size_t loract_static_scratch_bytes(void) { return (size_t)LORACT_STATIC_SCRATCH_BYTES; }
+
+int loract_lora_grad_static(const void* U_dev, const void* V_dev, int64_t m, int64_t n, int32_t k,
+                            int32_t factor_dtype, const void* dY_dev, int64_t n_out,
+                            const void* Blora_dev, int32_t r_lora, int32_t grad_dtype, float scale,
+                            float* dA_dev, void* stream) {
+  LoraPlan lp;
+  LORACT_TRY(make_lora_plan(m, n, k, n_out, r_lora, &lp));
+  if (lp.total > (size_t)LORACT_STATIC_SCRATCH_BYTES) {
+    g_host.last_hip_error = "loract_lora_grad_static: this shape needs " + std::to_string(lp.total) +
+                            " bytes of scratch, the built-in buffer holds " +
+                            std::to_string((size_t)LORACT_STATIC_SCRATCH_BYTES);
+    return LORACT_ERR_WORKSPACE_TOO_SMALL;
+  }
+  void* ws = nullptr;
+  LORACT_TRY(static_scratch_ptr(&ws));
+  // the partial results every kernel of the gradient reads were written by an earlier kernel of
+  // the same call, so nothing in the buffer has to start at zero
+  return loract_lora_grad(U_dev, V_dev, m, n, k, factor_dtype, dY_dev, n_out, Blora_dev, r_lora,
+                          grad_dtype, scale, dA_dev, ws, (size_t)LORACT_STATIC_SCRATCH_BYTES, stream);
 }
 
 int loract_gaussian_omega_t(void* omegaT_dev, int32_t l, int64_t n, int32_t dtype, uint64_t seed,

@@ -70,6 +70,21 @@ def test_sample_indices_rejects_bad_arguments():
     assert lib.loract_sample_indices(2 ** 31, 2, 0, buf) == -1
 
 
+def test_static_scratch_entry_rejects_oversized_shapes_on_the_host():
+    # a 65536-row gradient needs 30 MiB of scratch, the built-in buffer holds 16 MiB: refused
+    # before any pointer is touched or anything is enqueued (so this runs without a GPU)
+    lib = _lib.load()
+    assert lib.loract_static_scratch_bytes() == 16 << 20
+    need = ctypes.c_size_t(0)
+    assert lib.loract_lora_grad_workspace_bytes(65536, 4096, 256, 4096, 16, ctypes.byref(need)) == 0
+    assert need.value > lib.loract_static_scratch_bytes()
+    fake = ctypes.c_void_p(256)
+    rc = lib.loract_lora_grad_static(fake, fake, 65536, 4096, 256, 1, fake, 4096, fake, 16, 1, 1.0, fake, None)
+    assert rc == -2
+    assert b"16777216" in lib.loract_last_hip_error()
+    assert lib.loract_lora_grad_static(fake, fake, 0, 4096, 256, 1, fake, 4096, fake, 16, 1, 1.0, fake, None) == -1
+
+
 def _params(**kw):
     base = dict(m=1024, n=256, ldx=256, k=16, l=0, t=0, x_dtype=0, factor_dtype=0, seed=0)
     base.update(kw)
