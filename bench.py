@@ -139,7 +139,14 @@ def c5_stream(args, L, torch, np) -> int:
         "data": "synthetic",
         "config": {"workload": "c5stream: %d layers x 7 sites of 65536 x {4096 x6, 11008 x1} bf16, rank 256, "
                                "two HIP streams (generate || compress), double-buffered X" % args.layers},
+        "layers": args.layers, "sites": len(sites),
+        "full_configuration": bool(args.layers == 32),
         "compress_only_gbps": round(total_bytes / compress_only / 1e9, 2),
+        # two passes over X, the sampled rows, Y out and in, the factors: the algorithmic bytes of a
+        # compress as Algorithm 1 is written, against the 8 TB/s of the part
+        "compress_only_hbm_frac_two_pass": round(
+            sum(2 * m * widths[s] * 2 + k * widths[s] * 2 + 2 * m * k * 4 + (m + widths[s]) * k * 2
+                for _, s in sites) / compress_only / 1e9 / HBM_PEAK_GBS, 4),
         "compress_only_ms_per_site": round(compress_only * 1e3 / len(sites), 3),
         "rel_fro_err_min_max": [round(float(min(errs)), 5), round(float(max(errs)), 5)],
         "factor_bytes_kept": int(sum(u.numel() * 2 + v.numel() * 2 for u, v in factors)),
@@ -154,8 +161,9 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "c5", "coherent", "c5stream"])
-    ap.add_argument("--layers", type=int, default=2,
-                    help="c5stream only: decoder layers to stream (7 sites each; the full config is 32)")
+    ap.add_argument("--layers", type=int, default=32,
+                    help="c5stream only: decoder layers to stream (7 sites each; the configuration is 32 layers, "
+                         "fewer is a subsample of it and is labelled so)")
     ap.add_argument("--streams", type=int, default=3,
                     help="independent sites in flight for the `pipelined` figure (hardware queues per process: 4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -369,6 +377,62 @@ def main() -> int:
         pipelined = {"streams": nstreams, "us_per_site": round(us_site, 1),
                      "gbps": round(x_bytes / us_site / 1e3, 1), "bit_identical_to_single_stream": bool(same)}
 
+    # The same sites as HIP graphs: one captured site (compress + reconstruct + lora_grad) per stream,
+    # replayed round after round.  A graph launch costs the host one call per site instead of ~25,
+    # which removes the host's launch rate from the figure above.  Every replay is checked against
+    # the eager result (the library records kernels only: no copies, no memsets, ids in the kernel
+    # arguments), with eager work and synchronisations between replays.
+    pipelined_graph = None
+    if not args.no_comparator:
+        nstreams = min(args.streams, 4)
+        streams = [torch.cuda.Stream() for _ in range(nstreams)]
+        gheld, graphs = [], []
+        for st in streams:
+            bufs = (x.clone(), torch.empty_like(u), torch.empty_like(v), torch.empty_like(xhat),
+                    torch.empty_like(ga))
+            gheld.append(bufs)
+
+            def site(bufs=bufs):
+                xs, us, vs, xh, gs = bufs
+                L.loract_compress(xs, k, seed=w.seed, out=(us, vs))
+                L.loract_reconstruct(us, vs, out=xh)
+                L.loract_lora_grad(us, vs, dy, bl, scale=1.0, out=gs)
+
+            with torch.cuda.stream(st):
+                site()                      # workspaces and first-use set-up happen outside the capture
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                site()
+            graphs.append(g)
+        torch.cuda.synchronize()
+
+        def replay_round():
+            for st, g in zip(streams, graphs):
+                with torch.cuda.stream(st):
+                    g.replay()
+
+        identical = True
+        for rep in range(3):
+            for bufs in gheld:
+                bufs[1].zero_(); bufs[2].zero_(); bufs[3].zero_(); bufs[4].zero_()
+            step()                          # eager work between the replays
+            torch.cuda.synchronize()
+            replay_round()
+            torch.cuda.synchronize()
+            identical = identical and all(torch.equal(h[1], u) and torch.equal(h[2], v) and
+                                          torch.equal(h[3], xhat) and torch.equal(h[4], ga) for h in gheld)
+        tg0 = time.perf_counter()
+        for _ in range(args.steps):
+            replay_round()
+        torch.cuda.synchronize()
+        us_site_g = (time.perf_counter() - tg0) * 1e6 / (args.steps * nstreams)
+        pipelined_graph = {"streams": nstreams, "us_per_site": round(us_site_g, 1),
+                           "gbps": round(x_bytes / us_site_g / 1e3, 1),
+                           "site": "compress + reconstruct + lora_grad captured as one HIP graph per stream",
+                           "bit_identical_to_eager_on_every_checked_replay": bool(identical)}
+        del graphs, gheld
+
     # pre-norm unit (Section 3.3) at the same shape: bandwidth-bound row kernels
     gamma = torch.ones((n,), dtype=torch.float32, device="cuda")
     a_n, rms_n = L.loract_prenorm_forward(x, gamma)
@@ -426,6 +490,40 @@ def main() -> int:
                       "loract_compress_us": round(us_c, 1),
                       "speedup_vs_range_finder": round((us_rsvd - us_trunc) / us_c, 2)}
 
+    # Error against time: the power rounds of Algorithm 1 (t = 0, 1, 2) beside the randomized SVD it
+    # is compared with in Section 3.2 (Gaussian test matrix; q power rounds; with and without the
+    # oversampling of 8 columns that the comparator's truncation to rank k goes with).
+    error_vs_time = None
+    if not args.no_comparator:
+        x32n = torch.linalg.norm(x.float())
+
+        def measure(fn):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            reps = max(3, args.steps // 5)
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                uu, vv = fn()
+            e1.record()
+            torch.cuda.synchronize()
+            xr = L.loract_reconstruct(uu, vv)
+            e = float((torch.linalg.norm(xr.float() - x.float()) / x32n).item())
+            return round(e0.elapsed_time(e1) * 1e3 / reps, 1), round(e, 6)
+
+        rows = []
+        for t_it in (0, 1, 2):
+            us_t, e_t = measure(lambda: L.loract_compress(x, k, t=t_it, seed=w.seed))
+            rows.append({"method": "Algorithm 1, t = %d" % t_it, "us": us_t, "rel_fro_err": e_t})
+        for q_it, p_over in ((0, 0), (1, 0), (1, 8)):
+            us_t, e_t = measure(lambda: L.loract_rsvd(x, k, oversample=p_over, power_iters=q_it, seed=w.seed))
+            rows.append({"method": "randomized SVD, q = %d, oversampling %d" % (q_it, p_over), "us": us_t,
+                         "rel_fro_err": e_t})
+        error_vs_time = {"rank": k, "rank_k_floor": (round(float(w.extras["rank_k_floor"]), 6)
+                                                      if "rank_k_floor" in w.extras else None), "rows": rows}
+
     # accuracy of the timed outputs (cheap GPU-side figure; full parity lives in tests/)
     err = float((torch.linalg.norm(xhat.float() - x.float()) / torch.linalg.norm(x.float())).item())
 
@@ -454,6 +552,8 @@ def main() -> int:
         "roofline_streaming": roofline_streaming,
         "comparator": comparator,
         "pipelined": pipelined,
+        "pipelined_graph": pipelined_graph,
+        "error_vs_time": error_vs_time,
         "prenorm": prenorm,
         "kernels": kernels,
     }

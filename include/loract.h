@@ -114,6 +114,24 @@ int loract_compress(const void* X_dev, const loract_params* p, const int32_t* id
                     void* stream, int32_t* status_dev);
 
 /*
+ * Algorithm 1 with the rank chosen from the data.  The paper fixes k by hand and leaves adaptive
+ * rank selection to future work (Conclusion); the rule used here is the measure of Section 2: the
+ * number of kept dimensions when `energy` (0 < energy <= 1, Section 2 uses 0.9) of the energy --
+ * the sum of the singular values -- is retained.  It is evaluated inside the sketch: with Q an
+ * orthonormal basis of the l-column sketch (l = p->l sampled rows, 0 = p->k) and s_1 >= ... >= s_l the
+ * singular values of B = Q^T X, k_eff is the smallest count with s_1 + ... + s_k_eff >= energy *
+ * (s_1 + ... + s_l), at most p->k, and the factors are the k_eff leading singular triplets of B as
+ * in loract_compress with l > k.
+ * U_dev, V_dev  out, m x p->k and p->k x n as for loract_compress: columns of U and rows of V from
+ *               k_eff on are zero, so U V is the rank-k_eff product whatever slice the caller keeps.
+ * k_out_dev     out, int32 in device memory: k_eff.
+ * Workspace, indices, stream, status and errors as for loract_compress.
+ */
+int loract_compress_adaptive(const void* X_dev, const loract_params* p, const int32_t* idx_host,
+                             double energy, void* U_dev, void* V_dev, int32_t* k_out_dev,
+                             void* ws_dev, size_t ws_bytes, void* stream, int32_t* status_dev);
+
+/*
  * Backward pass, Section 3.1 Eq. (4): Xhat = U V.
  * U_dev m x k, V_dev k x n (contiguous, dtype factor_dtype); Xhat_dev out, m x n with leading
  * dimension ldxh >= n, dtype out_dtype.  No workspace.

@@ -9,6 +9,8 @@ What it follows (all citations are to the LoRAct paper, arXiv 2509.23472):
 * `decompose`        Section 3.2, Algorithm 1 (sampling-based orthogonal decomposition): the
                      sketch of A by its own sampled rows, optionally sharpened by t power
                      rounds, an orthonormal basis U of the sketch's range, and V = U^T A.
+* `decompose_adaptive`  the same with the rank chosen by the retained-energy count of Section 2
+                     (sum of singular values), measured inside the sketch.
 * `reconstruct`      Section 3.1, Eq. (4): A~ = U V.
 * `lora_grad`        Section 3.1, Eq. (4)-(5) applied to a LoRA down-projection: the weight
                      gradient contraction A~^T (dY B^T) * scale, with A~ rebuilt first exactly
@@ -171,6 +173,45 @@ def decompose(a: np.ndarray, k: int, t: int = 0, seed: int = 0,
         return q, b
     ub, s, vbt = np.linalg.svd(b, full_matrices=False)
     return q @ ub[:, :k], s[:k, None] * vbt[:k, :]
+
+
+def decompose_adaptive(a: np.ndarray, k_max: int, energy: float, t: int = 0, seed: int = 0,
+                       idx: Optional[Sequence[int]] = None, l: Optional[int] = None):
+    """Algorithm 1 with the rank chosen from the data (the paper's Conclusion leaves adaptive rank
+    selection to future work; the rule is the one Section 2 uses to measure how low-rank
+    activations are: the number of kept dimensions when `energy` of the energy, i.e. of the sum
+    of the singular values, is retained).
+
+    Reading: the energy is measured inside the sketch.  With Q an orthonormal basis of the
+    l-column sketch and s_1 >= ... >= s_l the singular values of B = Q^T A (those of the projected
+    matrix Q Q^T A), the rank is the smallest k with s_1 + ... + s_k >= energy * (s_1 + ... + s_l),
+    capped at k_max; the factors are then cut to that k as in `decompose` with l > k.  When every
+    row is sampled (l = min(m, n)) this is exactly the count Section 2 reports for A itself.
+
+    Returns (U, V, k, fractions) with U m x k, V k x n and fractions[j] = (s_1 + ... + s_{j+1}) /
+    (s_1 + ... + s_l).
+    """
+    a = np.asarray(a, dtype=np.float64)
+    m, n = a.shape
+    if l is None:
+        l = k_max
+    if not (1 <= k_max <= l <= min(m, n)) or not (0.0 < energy <= 1.0):
+        raise ValueError("need 1 <= k_max <= l <= min(m, n) and 0 < energy <= 1")
+    rows = sample_indices(m, l, seed) if idx is None else np.asarray(idx, dtype=np.int64)
+    if rows.shape != (l,):
+        raise ValueError("need exactly l sampled rows")
+    y = a @ a[rows, :].T
+    for _ in range(t):
+        q, _ = householder_qr(y)
+        y = a @ (a.T @ q)
+    q, _ = householder_qr(y)
+    b = q.T @ a
+    ub, s, vbt = np.linalg.svd(b, full_matrices=False)
+    fractions = np.cumsum(s) / np.sum(s)
+    reached = np.nonzero(fractions >= energy)[0]
+    k = int(reached[0]) + 1 if reached.size else l
+    k = min(k, k_max)
+    return q @ ub[:, :k], s[:k, None] * vbt[:k, :], k, fractions
 
 
 def reconstruct(u: np.ndarray, v: np.ndarray) -> np.ndarray:

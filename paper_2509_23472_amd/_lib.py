@@ -34,6 +34,8 @@ SIGNATURES = {
     "loract_sample_indices": (ctypes.c_int, [_i64, _i32, _u64, _P(_i32)]),
     "loract_workspace_bytes": (ctypes.c_int, [_P(LoractParams), _P(_sz)]),
     "loract_compress": (ctypes.c_int, [_vp, _P(LoractParams), _P(_i32), _vp, _vp, _vp, _sz, _vp, _vp]),
+    "loract_compress_adaptive": (ctypes.c_int, [_vp, _P(LoractParams), _P(_i32), ctypes.c_double, _vp, _vp, _vp,
+                                                _vp, _sz, _vp, _vp]),
     "loract_reconstruct": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _i32, _vp]),
     "loract_lora_grad_workspace_bytes": (ctypes.c_int, [_i64, _i64, _i32, _i64, _i32, _P(_sz)]),
     "loract_lora_grad": (ctypes.c_int, [_vp, _vp, _i64, _i64, _i32, _i32, _vp, _i64, _vp, _i32, _i32,

@@ -134,6 +134,38 @@ def loract_compress(x: torch.Tensor, k: int, t: int = 0, seed: int = 0,
     return u, v
 
 
+def loract_compress_adaptive(x: torch.Tensor, k_max: int, energy: float = 0.9, l: int = 0, t: int = 0,
+                             seed: int = 0, idx: Optional[Sequence[int]] = None,
+                             factor_dtype: Optional[torch.dtype] = None,
+                             status: Optional[torch.Tensor] = None
+                             ) -> Tuple[torch.Tensor, torch.Tensor, torch.Tensor]:
+    """Algorithm 1 with the rank chosen by the retained-energy count of Section 2 (sum of singular
+    values of the l x n factor), at most k_max.  Returns U (m x k_max), V (k_max x n) whose columns /
+    rows from the chosen rank on are zero, and the chosen rank as an int32 GPU tensor (read it when
+    convenient: nothing here synchronises)."""
+    _require_cuda(x)
+    lib = _lib.load()
+    p = make_params(x, k_max, l, t, seed, factor_dtype)
+    fdt = _torch_dtype(p.factor_dtype)
+    u = torch.empty((p.m, k_max), dtype=fdt, device=x.device)
+    v = torch.empty((k_max, p.n), dtype=fdt, device=x.device)
+    k_out = torch.zeros((1,), dtype=torch.int32, device=x.device)
+    ws = _workspace(loract_workspace_bytes(p), x.device)
+    idx_arr = None
+    if idx is not None:
+        n_idx = l if l else k_max
+        if len(idx) != n_idx:
+            raise ValueError("idx must hold l row ids (k_max when l is 0)")
+        idx_arr = (ctypes.c_int32 * n_idx)(*[int(i) for i in idx])
+    if status is not None and (status.dtype != torch.int32 or not status.is_cuda):
+        raise ValueError("status must be an int32 GPU tensor")
+    _check(lib.loract_compress_adaptive(x.data_ptr(), ctypes.byref(p), idx_arr, float(energy), u.data_ptr(),
+                                        v.data_ptr(), k_out.data_ptr(), ws.data_ptr(), ws.numel(),
+                                        _stream_ptr(), status.data_ptr() if status is not None else None),
+           "loract_compress_adaptive")
+    return u, v, k_out
+
+
 def loract_reconstruct(u: torch.Tensor, v: torch.Tensor, out_dtype: Optional[torch.dtype] = None,
                        out: Optional[torch.Tensor] = None) -> torch.Tensor:
     """Xhat = U V (Section 3.1, Eq. 4)."""

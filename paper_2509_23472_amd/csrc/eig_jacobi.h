@@ -15,8 +15,13 @@
 
 // A: l x l symmetric (overwritten, diagonal -> eigenvalues); W: l x l out (columns = eigenvectors);
 // Wk: l x k out = the k eigenvectors of largest eigenvalue, in descending order.
+// Adaptive rank (k_out != null): with s_i = sqrt(eigenvalue i) in descending order -- the singular
+// values of the factor whose Gram matrix A is -- only the first k_eff columns of Wk are filled,
+// k_eff = the smallest count with s_1 + ... + s_k_eff >= energy * (s_1 + ... + s_l), at most k;
+// the other columns are zero and *k_out = k_eff (the retained-energy count of Section 2).
 __global__ __launch_bounds__(EJ_THREADS) void jacobi_eig_kernel(double* A, double* W, double* Wk,
-                                                                int l, int k) {
+                                                                int l, int k, double energy,
+                                                                int32_t* k_out) {
   __shared__ double cs_c[LORACT_MAX_RANK / 2 + 1], cs_s[LORACT_MAX_RANK / 2 + 1];
   __shared__ int pr_p[LORACT_MAX_RANK / 2 + 1], pr_q[LORACT_MAX_RANK / 2 + 1];
   __shared__ double red[EJ_THREADS / 64];
@@ -117,14 +122,33 @@ __global__ __launch_bounds__(EJ_THREADS) void jacobi_eig_kernel(double* A, doubl
     order[rank] = i;
   }
   __syncthreads();
+  __shared__ int k_eff;
+  if (t == 0) {
+    int keep = k;
+    if (k_out) {
+      double total = 0.0;
+      for (int i = 0; i < l; ++i) total += sqrt(fmax(A[(int64_t)order[i] * l + order[i]], 0.0));
+      double run = 0.0;
+      keep = l;
+      for (int i = 0; i < l; ++i) {
+        run += sqrt(fmax(A[(int64_t)order[i] * l + order[i]], 0.0));
+        if (run >= energy * total) { keep = i + 1; break; }
+      }
+      if (keep > k) keep = k;
+      *k_out = keep;
+    }
+    k_eff = keep;
+  }
+  __syncthreads();
   for (int e = t; e < l * k; e += EJ_THREADS) {
     const int r = e / k, c = e - r * k;
-    Wk[e] = W[(int64_t)r * l + order[c]];
+    Wk[e] = c < k_eff ? W[(int64_t)r * l + order[c]] : 0.0;
   }
 }
 
-static int launch_jacobi_eig(hipStream_t s, double* A, double* W, double* Wk, int l, int k) {
+static int launch_jacobi_eig(hipStream_t s, double* A, double* W, double* Wk, int l, int k,
+                             double energy = 1.0, int32_t* k_out = nullptr) {
   if (l < 1 || l > LORACT_MAX_RANK || k < 1 || k > l) return LORACT_ERR_INVALID_ARG;
-  LORACT_LAUNCH("jacobi_eig", s, jacobi_eig_kernel, dim3(1), dim3(EJ_THREADS), 0, A, W, Wk, l, k);
+  LORACT_LAUNCH("jacobi_eig", s, jacobi_eig_kernel, dim3(1), dim3(EJ_THREADS), 0, A, W, Wk, l, k, energy, k_out);
   return LORACT_OK;
 }

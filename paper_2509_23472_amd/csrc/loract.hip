@@ -116,7 +116,7 @@ static int validate_params(const loract_params* p, bool rsvd, int* l_out) {
   return LORACT_OK;
 }
 
-static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
+static int make_plan(const loract_params* p, bool rsvd, Plan* pl, bool truncate_always = false) {
   int l = 0;
   LORACT_TRY(validate_params(p, rsvd, &l));
   pl->l = l;
@@ -144,8 +144,9 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
   if (pl->bf16_path) dpart = std::max(dpart, (size_t)pl->kp * pl->kp * 8);   // E^2 of the degree-4 finish
+  const bool trunc = l > p->k || truncate_always;
   pl->bgram_splits = 1;
-  if (l > p->k) {
+  if (trunc) {
     pl->bgram_splits = pick_splits(lt * lt, n, 256);
     dpart = std::max(dpart, (size_t)pl->bgram_splits * l * l * 8);
   }
@@ -161,8 +162,8 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl) {
   pl->off_fpart = take(fpart);
   const bool need_zt = p->t > 0 || rsvd;
   pl->off_zt = take(need_zt ? (size_t)l * n * (pl->bf16_path ? 2 : 8) : 0);
-  pl->off_bmat = take(l > p->k ? (size_t)l * n * (pl->bf16_path ? 4 : 8) : 0);
-  pl->off_eig = take(l > p->k ? (size_t)3 * l * l * 8 : 0);
+  pl->off_bmat = take(trunc ? (size_t)l * n * (pl->bf16_path ? 4 : 8) : 0);
+  pl->off_eig = take(trunc ? (size_t)3 * l * l * 8 : 0);
   pl->off_omega = take(rsvd ? (size_t)l * n * (pl->bf16_path ? 2 : 4) : 0);
   pl->total = off;
   return LORACT_OK;
@@ -352,9 +353,10 @@ static int project(const Ctx& c, const void* Q, int q_ek, void* Bt, int out_ek) 
 }
 
 static int check_common(const void* X, const loract_params* p, void* U, void* V, void* ws,
-                        size_t ws_bytes, bool rsvd, Ctx* c, hipStream_t s, int32_t* status) {
+                        size_t ws_bytes, bool rsvd, Ctx* c, hipStream_t s, int32_t* status,
+                        bool truncate_always = false) {
   if (!X || !U || !V) return LORACT_ERR_INVALID_ARG;
-  LORACT_TRY(make_plan(p, rsvd, &c->pl));
+  LORACT_TRY(make_plan(p, rsvd, &c->pl, truncate_always));
   if (!ws || ws_bytes < c->pl.total) return LORACT_ERR_WORKSPACE_TOO_SMALL;
   if (((uintptr_t)ws) % 16 != 0) return LORACT_ERR_INVALID_ARG;
   c->s = s;
@@ -467,11 +469,12 @@ int loract_sample_indices(int64_t m, int32_t l, uint64_t seed, int32_t* idx_host
 int loract_workspace_bytes(const loract_params* p, size_t* bytes) {
   if (!bytes) return LORACT_ERR_INVALID_ARG;
   Plan pl;
-  // the RSVD layout is a superset of the compress layout, so one size serves both calls
+  // the RSVD layout with the truncation buffers is a superset of every other layout, so one
+  // size serves loract_compress, loract_compress_adaptive and loract_rsvd
   loract_params q;
   if (!p) return LORACT_ERR_INVALID_ARG;
   q = *p;
-  int rc = make_plan(&q, true, &pl);
+  int rc = make_plan(&q, true, &pl, true);
   if (rc != LORACT_OK) return rc;
   *bytes = pl.total;
   return LORACT_OK;
@@ -481,7 +484,8 @@ int loract_workspace_bytes(const loract_params* p, size_t* bytes) {
 // factors of the k leading singular triplets of B: U = Q W_k, V = W_k^T B, where the columns of
 // W_k are the k leading eigenvectors of B B^T (Section 3.2; the setting of Theorem 4.3 when the
 // sketch comes from l sampled rows).
-static int truncate_factors(const Ctx& c, void* Y, void* tmp, void* U_dev, void* V_dev) {
+static int truncate_factors(const Ctx& c, void* Y, void* tmp, void* U_dev, void* V_dev,
+                            double energy = 1.0, int32_t* k_out = nullptr) {
   const loract_params* p = c.p;
   hipStream_t s = c.s;
   const int64_t m = p->m, n = p->n;
@@ -507,7 +511,7 @@ static int truncate_factors(const Ctx& c, void* Y, void* tmp, void* U_dev, void*
   double* Wk = eigW + (size_t)l * l;
   LORACT_TRY(launch_gemm_f64("truncate_bbt", s, Bmat, n, 1, b_ek, Bmat, n, 1, b_ek, nullptr, l, l, n, 1.0,
                              eigA, l, EK_F64, c.pl.bgram_splits, ws_ptr<double>(c, c.pl.off_dpart)));
-  LORACT_TRY(launch_jacobi_eig(s, eigA, eigW, Wk, l, k));
+  LORACT_TRY(launch_jacobi_eig(s, eigA, eigW, Wk, l, k, energy, k_out));
   // U = Q W_k (m x k),  V = W_k^T B (k x n)
   LORACT_TRY(launch_gemm_f64("truncate_qw", s, Q, l, 1, q_ek, Wk, k, 0, EK_F64, nullptr, m, k, l, 1.0,
                              U_dev, k, f_ek, 1, nullptr));
@@ -515,12 +519,14 @@ static int truncate_factors(const Ctx& c, void* Y, void* tmp, void* U_dev, void*
                          V_dev, n, f_ek, 1, nullptr);
 }
 
-int loract_compress(const void* X_dev, const loract_params* p, const int32_t* idx_host,
-                    void* U_dev, void* V_dev, void* ws_dev, size_t ws_bytes, void* stream,
-                    int32_t* status_dev) {
+// Shared by loract_compress and loract_compress_adaptive (k_out != null: the rank is chosen from
+// the singular values of the l x n factor, see loract.h).
+static int compress_impl(const void* X_dev, const loract_params* p, const int32_t* idx_host,
+                         void* U_dev, void* V_dev, void* ws_dev, size_t ws_bytes, void* stream,
+                         int32_t* status_dev, double energy, int32_t* k_out) {
   Ctx c;
   hipStream_t s = (hipStream_t)stream;
-  LORACT_TRY(check_common(X_dev, p, U_dev, V_dev, ws_dev, ws_bytes, false, &c, s, status_dev));
+  LORACT_TRY(check_common(X_dev, p, U_dev, V_dev, ws_dev, ws_bytes, false, &c, s, status_dev, k_out != nullptr));
   const int k = p->k, l = c.pl.l;
   IdxPack pack;
   memset(&pack, 0, sizeof(pack));
@@ -544,8 +550,22 @@ int loract_compress(const void* X_dev, const loract_params* p, const int32_t* id
     LORACT_TRY(sketch(c, X_dev, p->ldx, idx_dev, Y));          // Y = X X_S^T
   }
   LORACT_TRY(power_iterations(c, Y, tmp));                // t power rounds
-  if (l == k) return finish_factors(c, Y, tmp, U_dev, V_dev);   // U = orth(Y), V = U^T X
-  return truncate_factors(c, Y, tmp, U_dev, V_dev);       // l > k sampled rows: rank-k truncation
+  if (l == k && !k_out) return finish_factors(c, Y, tmp, U_dev, V_dev);   // U = orth(Y), V = U^T X
+  return truncate_factors(c, Y, tmp, U_dev, V_dev, energy, k_out);  // l > k sampled rows, or adaptive rank
+}
+
+int loract_compress(const void* X_dev, const loract_params* p, const int32_t* idx_host,
+                    void* U_dev, void* V_dev, void* ws_dev, size_t ws_bytes, void* stream,
+                    int32_t* status_dev) {
+  return compress_impl(X_dev, p, idx_host, U_dev, V_dev, ws_dev, ws_bytes, stream, status_dev, 1.0, nullptr);
+}
+
+int loract_compress_adaptive(const void* X_dev, const loract_params* p, const int32_t* idx_host,
+                             double energy, void* U_dev, void* V_dev, int32_t* k_out_dev,
+                             void* ws_dev, size_t ws_bytes, void* stream, int32_t* status_dev) {
+  if (!k_out_dev || !(energy > 0.0 && energy <= 1.0)) return LORACT_ERR_INVALID_ARG;
+  return compress_impl(X_dev, p, idx_host, U_dev, V_dev, ws_dev, ws_bytes, stream, status_dev, energy,
+                       k_out_dev);
 }
 
 int loract_reconstruct(const void* U_dev, const void* V_dev, int64_t m, int64_t n, int32_t k,

@@ -456,3 +456,62 @@ def test_planted_truncation_mistakes_violate_the_oversampled_pin():
     assert orc.rel_fro(good, best) <= 1e-9
     assert orc.rel_fro(first_columns, best) > 1e-3
     assert orc.rel_fro(unscaled, best) > 1e-3
+
+
+# ----------------------------------------------------------------------------- adaptive rank
+
+
+def _orthonormal_factors(m, n, r, seed):
+    rng = np.random.default_rng(seed)
+    u, _ = np.linalg.qr(rng.standard_normal((m, r)))
+    v, _ = np.linalg.qr(rng.standard_normal((n, r)))
+    return u, v
+
+
+def test_adaptive_rank_worked_example():
+    # A with singular values (3, 2, 1, 1, 1) exactly and l >= 5 sampled rows: the sketch spans the
+    # whole row space, B = Q^T A has the singular values of A, and the retained fractions of the
+    # energy (sum of singular values, Section 2) are 3/8, 5/8, 6/8, 7/8, 8/8.
+    u, v = _orthonormal_factors(40, 30, 5, 1)
+    a = (u * np.array([3.0, 2.0, 1.0, 1.0, 1.0])[None, :]) @ v.T
+    for energy, want in [(0.3, 1), (0.375 - 1e-9, 1), (0.5, 2), (0.7, 3), (0.8, 4), (0.9, 5), (1.0 - 1e-9, 5)]:
+        uu, vv, k, frac = orc.decompose_adaptive(a, 8, energy, seed=3, l=8)
+        assert k == want, (energy, k)
+        assert uu.shape == (40, k) and vv.shape == (k, 30)
+        assert np.allclose(frac[:5], [3 / 8, 5 / 8, 6 / 8, 7 / 8, 1.0], atol=1e-12)
+        # the factors are the k leading singular triplets of A itself here
+        best = (u[:, :k] * np.array([3.0, 2.0, 1.0, 1.0, 1.0])[None, :k]) @ v[:, :k].T
+        if want in (1, 2, 5):      # (the triple singular value 1 has no unique truncation in between)
+            assert np.allclose(uu @ vv, best, atol=1e-10)
+    # the cap: never more than k_max columns
+    assert orc.decompose_adaptive(a, 3, 0.99, seed=3, l=8)[2] == 3
+
+
+@pytest.mark.parametrize("m,n,l", [(60, 24, 10), (35, 50, 20)])
+def test_adaptive_rank_is_the_count_on_the_projected_matrix(m, n, l):
+    # brute force: singular values of P_Y A with P_Y from the pseudo-inverse of the sketch, no QR
+    a = _tiny(m, n, 7)
+    for seed in range(4):
+        rows = orc.sample_indices(m, l, seed)
+        y = a @ a[rows, :].T
+        p_y = y @ np.linalg.pinv(y)
+        s = np.linalg.svd(p_y @ a, compute_uv=False)[:l]
+        for energy in (0.5, 0.8, 0.9, 0.97):
+            want = int(np.nonzero(np.cumsum(s) / np.sum(s) >= energy)[0][0]) + 1
+            uu, vv, k, _ = orc.decompose_adaptive(a, l, energy, seed=seed)
+            assert k == want
+            # and the factors are those of the fixed-rank call with that k
+            u2, v2 = orc.decompose(a, k, seed=seed, l=l)
+            assert np.allclose(uu @ vv, u2 @ v2, atol=1e-10 * np.abs(a).max())
+
+
+def test_adaptive_rank_with_every_row_sampled_is_the_count_of_section_2():
+    a = _tiny(18, 30, 5, decay=0.6)
+    s = np.linalg.svd(a, compute_uv=False)
+    ks = []
+    for energy in (0.5, 0.9, 0.99):
+        want = int(np.nonzero(np.cumsum(s) / np.sum(s) >= energy)[0][0]) + 1
+        k = orc.decompose_adaptive(a, 18, energy, idx=np.arange(18))[2]
+        assert k == want
+        ks.append(k)
+    assert ks == sorted(ks)                  # more energy never needs fewer dimensions
