@@ -163,7 +163,8 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl, bool truncate_
   const bool need_zt = p->t > 0 || rsvd;
   pl->off_zt = take(need_zt ? (size_t)l * n * (pl->bf16_path ? 2 : 8) : 0);
   pl->off_bmat = take(trunc ? (size_t)l * n * (pl->bf16_path ? 4 : 8) : 0);
-  pl->off_eig = take(trunc ? (size_t)3 * l * l * 8 : 0);
+  // the Gram matrix of the l x n factor, the eigensolver's work matrix, the k leading eigenvectors
+  pl->off_eig = take(trunc ? ((size_t)2 * l * l + ej_work_doubles(l)) * 8 : 0);
   pl->off_omega = take(rsvd ? (size_t)l * n * (pl->bf16_path ? 2 : 4) : 0);
   pl->total = off;
   return LORACT_OK;
@@ -508,7 +509,7 @@ static int truncate_factors(const Ctx& c, void* Y, void* tmp, void* U_dev, void*
   }
   double* eigA = ws_ptr<double>(c, c.pl.off_eig);
   double* eigW = eigA + (size_t)l * l;
-  double* Wk = eigW + (size_t)l * l;
+  double* Wk = eigW + ej_work_doubles(l);
   LORACT_TRY(launch_gemm_f64("truncate_bbt", s, Bmat, n, 1, b_ek, Bmat, n, 1, b_ek, nullptr, l, l, n, 1.0,
                              eigA, l, EK_F64, c.pl.bgram_splits, ws_ptr<double>(c, c.pl.off_dpart)));
   LORACT_TRY(launch_jacobi_eig(s, eigA, eigW, Wk, l, k, energy, k_out));
