@@ -280,7 +280,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   // round 1: Q1 = Y R^{-1} (fp32, plus a bf16 copy for a possible Newton-Schulz finish)
   ch.round = 1;
   ch.ready = fused_solve_enabled() ? ns_flag + 1 : nullptr;     // progress word of the fused launch
-  const bool fused = chol_trsm_fusable(ch);
+  const bool fused = chol_trsm_fusable(ch, m);
   LORACT_TRY(launch_gram_mfma(c.s, Y, kp, m, kp, l, part, G, Gbak, nullptr, nullptr, fused ? ch.ready : nullptr));
   t.Y = Y; t.ldy = kp; t.Q = tmp; t.ldq = kp; t.out_ek = EK_F32; t.out_cols = kp;
   t.Qb = ns_ok ? Q1b : nullptr; t.ldqb = kp; t.skip_flag = nullptr;
@@ -293,7 +293,7 @@ static int orthonormalise_mfma(const Ctx& c, const float* Y, float* tmp, void* Q
   // round 2: either Q = Q1 (I - E/2) when E = Q1^T Q1 - I is small, or a second Cholesky QR
   double* ns_e2 = ws_ptr<double>(c, c.pl.off_flag) + 8;      // after the flag word
   ch.round = 2;
-  const bool fused2 = chol_trsm_fusable(ch);
+  const bool fused2 = chol_trsm_fusable(ch, m);
   LORACT_TRY(launch_gram_mfma(c.s, tmp, kp, m, kp, l, part, G, nullptr, ns_ok ? nsT : nullptr, ns_e2,
                               fused2 ? ch.ready : nullptr));
   ch.ns_e2 = ns_e2; ch.ns_e2_count = 64 * gram_nblocks(kp); ch.ns_flag = ns_flag;

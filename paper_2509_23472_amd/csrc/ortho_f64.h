@@ -995,8 +995,8 @@ struct TrsmArgs {
 // A change of the attempt number sends the workgroup back to J = 0.  `wg` is the workgroup's index
 // among the solving workgroups, `lds` its dynamic LDS.
 template <int NJ, int WAVES, bool FUSED>
-__device__ inline void trsm_body(const TrsmArgs& g, const int wg, double* trsm_lds, const int32_t* ready,
-                                 int32_t* status) {
+__device__ inline void trsm_body(const TrsmArgs& g, const int first_strip, const int strip_stride,
+                                 double* trsm_lds, const int32_t* ready, int32_t* status) {
   constexpr int J0 = FUSED ? 0 : TRSM_J0(NJ);
   constexpr int PK = 8 * J0 * (J0 + 1) + 2;           // pitch of the side-by-side array, in doubles
   constexpr int PR = 16 * NJ + 2;                     // pitch of a double-buffer half
@@ -1006,11 +1006,7 @@ __device__ inline void trsm_body(const TrsmArgs& g, const int wg, double* trsm_l
   if (g.skip_flag && *g.skip_flag != 0) return;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int lc = lane & 15, lr = lane >> 4;
-  const int64_t row = (int64_t)wg * (16 * WAVES) + wave * 16 + lc;
-  const bool rok = row < g.m;
-  // every row of the wave exists: its store instructions per step can be counted
-  const bool full_wave = (int64_t)wg * (16 * WAVES) + wave * 16 + 15 < g.m;
-  const float* yrow = g.Y + (rok ? row : 0) * g.ldy;   // rows past m read row 0 and are never stored
+  const int nstrips = (int)((g.m + 16 * WAVES - 1) / (16 * WAVES));
   // 4 consecutive output columns per lane can be stored as one vector
   const bool vec_ok = (g.ldq & 3) == 0 && ((uintptr_t)g.Q & 15) == 0 &&
                       (!g.Qb || ((g.ldqb & 3) == 0 && ((uintptr_t)g.Qb & 7) == 0));
@@ -1057,7 +1053,18 @@ __device__ inline void trsm_body(const TrsmArgs& g, const int wg, double* trsm_l
   f64x4 qb[NJ];
   float ycur[4], ynext[4];
   int att = 0;
+  int known = 0;                       // FUSED: the progress word as last seen (uniform in the workgroup)
   bool restart_solve;
+  // A workgroup takes the strips first_strip, first_strip + strip_stride, ... of 16 WAVES rows one
+  // after the other (FUSED: fewer workgroups than strips when the matrix is tall; once the progress
+  // word has been seen complete no strip polls again).  A restart of the factorisation sends the
+  // workgroup back to its first strip: everything it wrote so far belongs to the abandoned attempt.
+  for (int strip = first_strip; strip < nstrips; strip += strip_stride) {
+  const int64_t row = (int64_t)strip * (16 * WAVES) + wave * 16 + lc;
+  const bool rok = row < g.m;
+  // every row of the wave exists: its store instructions per step can be counted
+  const bool full_wave = (int64_t)strip * (16 * WAVES) + wave * 16 + 15 < g.m;
+  const float* yrow = g.Y + (rok ? row : 0) * g.ldy;   // rows past m read row 0 and are never stored
   do {
     restart_solve = false;
     bool next_copied = false;
@@ -1067,10 +1074,14 @@ __device__ inline void trsm_body(const TrsmArgs& g, const int wg, double* trsm_l
     for (int J = 0; J < NJ; ++J) {
       if (FUSED) {
         if (restart_solve) continue;                     // (uniform) the attempt changed: drain the unrolled loop
-        const int f = wait_panel(J, att);
-        if (f < 0) {                                     // the factorisation never got here: give up, flagged
-          if (t == 0 && status) atomicOr(status, LORACT_STATUS_INTERNAL);
-          return;
+        int f = known;
+        if ((f >> CF_ATTEMPT_SHIFT) != att || (f & 0xffff) <= J) {
+          f = wait_panel(J, att);
+          if (f < 0) {                                   // the factorisation never got here: give up, flagged
+            if (t == 0 && status) atomicOr(status, LORACT_STATUS_INTERNAL);
+            return;
+          }
+          known = f;
         }
         if ((f >> CF_ATTEMPT_SHIFT) != att) { att = f >> CF_ATTEMPT_SHIFT; restart_solve = true; continue; }
         if (!next_copied) copy_panel(J, ring + (J & 1) * 16 * PR, PR);
@@ -1153,13 +1164,18 @@ __device__ inline void trsm_body(const TrsmArgs& g, const int wg, double* trsm_l
         sb_barrier_lds();
       }
     }
-  } while (FUSED && restart_solve);
+  } while (FUSED && restart_solve && strip == first_strip);
+  if (FUSED) {
+    sb_barrier_lds();                  // this strip's last reads of the buffer halves precede the next strip's copies
+    if (restart_solve) strip = first_strip - strip_stride;      // (uniform) back to the first strip
+  }
+  }
 }
 
 template <int NJ, int WAVES>
 __global__ __launch_bounds__(64 * WAVES) void trsm_apply_kernel(TrsmArgs g) {
   extern __shared__ __attribute__((aligned(16))) double trsm_lds[];
-  trsm_body<NJ, WAVES, false>(g, blockIdx.x, trsm_lds, nullptr, nullptr);
+  trsm_body<NJ, WAVES, false>(g, blockIdx.x, gridDim.x, trsm_lds, nullptr, nullptr);
 }
 
 template <int NJ, int WAVES, bool FUSED>
@@ -1204,7 +1220,7 @@ __global__ __launch_bounds__(CR_THREADS) void chol_trsm_fused_kernel(CholArgs c,
     __syncthreads();
   }
   if (blockIdx.x == 0) chol_reg_body<SLOTS, true>(c, ptld, fused_lds);
-  else trsm_body<NJ, CR_THREADS / 64, true>(g, (int)blockIdx.x - 1, fused_lds, c.ready, c.status);
+  else trsm_body<NJ, CR_THREADS / 64, true>(g, (int)blockIdx.x - 1, (int)gridDim.x - 1, fused_lds, c.ready, c.status);
 }
 
 // Few rows: 64 per workgroup so that more CUs take part; many rows: 128, which halves the panel
@@ -1441,15 +1457,21 @@ static int launch_chol_blocked(hipStream_t s, CholArgs a) {
 template <int SLOTS, int NJ>
 static int launch_chol_trsm_fused_nj(hipStream_t s, const CholArgs& c, const TrsmArgs& g) {
   const int ptld = chol_reg_ptld(c.kp);
-  const size_t lds = std::max(chol_reg_lds_bytes(c.kp), trsm_lds_bytes<NJ, CR_THREADS / 64, true>());
+  // At least 81 KB: one workgroup per CU, so that the factorising workgroup -- whose first wave is
+  // the critical path of the whole launch -- never shares its CU's issue slots with solving
+  // workgroups (measured at 65536 rows: 235 us with two workgroups per CU, against 139 us for the two
+  // separate launches).
+  const size_t lds = std::max<size_t>(std::max(chol_reg_lds_bytes(c.kp), trsm_lds_bytes<NJ, CR_THREADS / 64, true>()),
+                                      81 * 1024);
   static std::atomic<bool> attr_done{false};
-  if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
+  if (!attr_done.load(std::memory_order_acquire)) {
     hipError_t e = hipFuncSetAttribute((const void*)chol_trsm_fused_kernel<SLOTS, NJ>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(fused factor-and-solve LDS)");
     attr_done.store(true, std::memory_order_release);
   }
-  const unsigned solvers = (unsigned)ceil_div64(g.m, 16 * (CR_THREADS / 64));
+  // one solving workgroup per CU beside the factorising one; a tall matrix gives each several strips
+  const unsigned solvers = (unsigned)std::min<int64_t>(ceil_div64(g.m, 16 * (CR_THREADS / 64)), 255);
   LORACT_LAUNCH("chol_trsm", s, (chol_trsm_fused_kernel<SLOTS, NJ>), dim3(1 + solvers), dim3(CR_THREADS), lds,
                 c, ptld, g);
   return LORACT_OK;
@@ -1457,7 +1479,8 @@ static int launch_chol_trsm_fused_nj(hipStream_t s, const CholArgs& c, const Trs
 
 // One launch per round when the register-resident factorisation applies (kp <= 256; round 1:
 // unshifted first attempt); c.ready must have been cleared by an earlier kernel.
-static bool chol_trsm_fusable(const CholArgs& c) {
+static bool chol_trsm_fusable(const CholArgs& c, int64_t m) {
+  (void)m;
   if (c.kp > 256 || !c.ready) return false;
   return c.round == 2 || (c.unshifted_thresh > 0.0 && c.G_backup);
 }
