@@ -59,6 +59,9 @@ def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: i
         "gram": 2.0 * m * kp * kp * 0.75,        # lower 64-blocks only
         "trsm_apply": 1.0 * m * kp * kp + 2.0 * m * kp * 16,
         "chol": kp ** 3 / 3.0,
+        # factorisation and triangular solve of a round in one launch (round 2 usually ends at once:
+        # the mean over its two launches per step is what `launches` divides)
+        "chol_trsm": (kp ** 3 / 3.0 + 1.0 * m * kp * kp + 2.0 * m * kp * 16) / max(launches, 1.0),
         # degree-4 finish of round 2: E^2, then E^3 and E^4 (float64 products of kp x kp matrices)
         "ns_poly_square": 2.0 * kp ** 3,
         "ns_poly_finish": 4.0 * kp ** 3,
@@ -324,10 +327,15 @@ def main() -> int:
         achieved, peak = d_amount / d_avg_s / 1e9, HBM_PEAK_GBS
     else:
         achieved, peak = d_amount / d_avg_s / 1e12, FP64_VECTOR_PEAK_TFLOPS
+    # HBM bytes per launch from the committed rocprofv3 --pmc summary, only if that summary was taken
+    # from this very build of the library (same source hash); otherwise null
     traffic = None
     if os.path.exists(args.traffic_json):
         try:
-            traffic = json.load(open(args.traffic_json)).get(args.workload, {}).get(dom)
+            from paper_2509_23472_amd.build import source_hash
+            tj = json.load(open(args.traffic_json))
+            if tj.get("source_hash") == source_hash():
+                traffic = tj.get(args.workload, {}).get(dom)
         except Exception:
             traffic = None
     roofline = {"kernel": dom, "bound": d_bound, "achieved": round(achieved, 2), "peak": peak,

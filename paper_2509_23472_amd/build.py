@@ -24,6 +24,20 @@ def hipcc_path() -> str:
     raise RuntimeError("hipcc not found")
 
 
+def source_hash() -> str:
+    """sha256 over the library's sources (csrc/ and the public header), in name order: identifies
+    the build a profile was taken from."""
+    import hashlib
+    h = hashlib.sha256()
+    files = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith((".h", ".hip")))
+    files.append(os.path.join(os.path.dirname(PKG_DIR), "include", "loract.h"))
+    for path in files:
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as fh:
+            h.update(fh.read())
+    return h.hexdigest()[:16]
+
+
 def build_library(verbose: bool = True) -> str:
     """Compile every HIP source into paper_2509_23472_amd/libloract.so and return its path."""
     sources = sorted(os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".hip"))
