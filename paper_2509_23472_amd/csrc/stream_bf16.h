@@ -732,11 +732,11 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
 // that two workgroups share a CU (one hides the other's waits) and the partial tiles stay small.
 // Wider Q: one workgroup per CU, three stages of 128 columns, or for tall matrices (where the
 // partial tiles are small against X) eight waves on 256 columns with two stages.
-static inline void project_shape_for(int l, int64_t m, int* ntq, int* ntx, int* stages, int* wn) {
+static inline void project_shape_for(int l, int64_t m, int64_t n, int* ntq, int* ntx, int* stages, int* wn) {
   *wn = 2;
   if (l <= 64) { *ntq = 1; *ntx = 2; *stages = 2; }
   else if (l <= 128) { *ntq = 2; *ntx = 2; *stages = 2; }
-  else if (m < 32768) { *ntq = 4; *ntx = 2; *stages = 3; }
+  else if (m < 32768 || n < 1024) { *ntq = 4; *ntx = 2; *stages = 3; }   // (a narrow X, as in the LoRA gradient, has no use for 256-column tiles)
   else { *ntq = 4; *ntx = 2; *stages = 2; *wn = 4; }
 }
 static size_t project_lds_bytes(int ntq, int ntx, int stages, int wn) {
@@ -745,7 +745,7 @@ static size_t project_lds_bytes(int ntq, int ntx, int stages, int wn) {
 // Fills in the work split of a projection (everything the kernels derive their indexing from).
 static void project_plan(ProjectArgs* g) {
   int ntq, ntx, stages, wn;
-  project_shape_for(g->l, g->m, &ntq, &ntx, &stages, &wn);
+  project_shape_for(g->l, g->m, g->n, &ntq, &ntx, &stages, &wn);
   g->bmq = 64 * ntq;
   g->bnx = 32 * ntx * wn;
   g->slabs = (int)ceil_div64(g->m, SB_BK);
@@ -791,7 +791,7 @@ template <int ROLE>
 static int launch_project_role(hipStream_t s, const ProjectArgs& g, const char* name) {
   if (g.l <= 64) return launch_project_shape<1, 2, 2, 2, ROLE>(s, g, name);
   if (g.l <= 128) return launch_project_shape<2, 2, 2, 2, ROLE>(s, g, name);
-  if (g.m < 32768) return launch_project_shape<4, 2, 3, 2, ROLE>(s, g, name);
+  if (g.m < 32768 || g.n < 1024) return launch_project_shape<4, 2, 3, 2, ROLE>(s, g, name);
   return launch_project_shape<4, 2, 2, 4, ROLE>(s, g, name);
 }
 static int launch_project_main(hipStream_t s, const ProjectArgs& g, const char* name, int role) {
