@@ -26,7 +26,10 @@
 // lane i of the group owning rows i, i + 16, ...; the dot product is summed inside the group by
 // four exchange steps.  Up to l = 141 G lives in LDS (160 KB); above, in a global work buffer that
 // stays in L2 (an order of magnitude slower: every round then moves the whole matrix through the
-// CU once; measured 2.6 ms at l = 136, 13 sweeps, against 40 ms at l = 264).
+// CU once; measured 2.6 ms at l = 136, 13 sweeps, against 40 ms at l = 264).  A round moves every
+// column through LDS once (2 l^2 x 8 bytes at 128 bytes per clock: about 1 us at l = 136), which
+// is most of its cost; 8 lanes per pair, so that the 68 pairs of a round at l = 136 run in one
+// pass instead of two, moves the same bytes with longer chains per lane and was slower (4.3 ms).
 #pragma once
 #include "common.h"
 

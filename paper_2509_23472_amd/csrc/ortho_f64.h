@@ -1479,10 +1479,15 @@ static int launch_chol_trsm_fused_nj(hipStream_t s, const CholArgs& c, const Trs
 
 // One launch per round when the register-resident factorisation applies (kp <= 256; round 1:
 // unshifted first attempt); c.ready must have been cleared by an earlier kernel.
+// A solving workgroup works strip by strip and a strip needs every panel, so only its first strip
+// overlaps the factorisation.  Beyond 32768 rows (more than eight strips per workgroup) that gain
+// is smaller than what the one-workgroup-per-CU solver of the fused launch loses against the plain
+// one (measured at 65536 rows, 256 columns: 206 us fused, 190 us as two launches).  Round 2
+// normally has nothing to factor, and there the single launch that decides for itself always wins.
 static bool chol_trsm_fusable(const CholArgs& c, int64_t m) {
-  (void)m;
   if (c.kp > 256 || !c.ready) return false;
-  return c.round == 2 || (c.unshifted_thresh > 0.0 && c.G_backup);
+  if (c.round == 2) return true;
+  return m <= 32768 && c.unshifted_thresh > 0.0 && c.G_backup;
 }
 static int launch_chol_trsm_fused(hipStream_t s, CholArgs c, const TrsmArgs& g) {
   c.tol = ((double)c.k * 5.9604644775390625e-08) * ((double)c.k * 5.9604644775390625e-08);

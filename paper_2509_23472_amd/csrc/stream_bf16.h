@@ -373,6 +373,35 @@ static inline bool sb_aligned(const void* p, int64_t ld) {
   return (((uintptr_t)p) % 16 == 0) && (ld % 8 == 0);
 }
 
+// Which share of the work a workgroup takes.  The projection and the reconstruction cut a list of
+// (output tile, step) items, tile major, into equal contiguous shares, one per workgroup; at step i
+// a share that begins at item b reads block (b + i) mod period of the operand every tile re-reads
+// (the basis Q, the factor U).  Workgroups are handed to the eight XCDs in turn (workgroup B runs
+// on XCD B mod 8) and each XCD has an L2 of its own, so the shares are sorted by b mod period and
+// dealt out in eight consecutive runs: the workgroups of one XCD then walk through the same blocks
+// of that operand at about the same time and fetch each of them into their L2 once, instead of once
+// per workgroup.  share_of[B] = share of workgroup B; any permutation is correct, this one is fast.
+#define SB_MAX_WGS 512
+static bool sb_xcd_order_enabled() {
+  static const bool on = [] { const char* e = getenv("LORACT_XCD_ORDER"); return !(e && e[0] == '0'); }();
+  return on;
+}
+static void sb_xcd_share_order(int64_t items, int wgs, int64_t period, unsigned short* share_of) {
+  int order[SB_MAX_WGS];
+  int64_t key[SB_MAX_WGS];
+  for (int w = 0; w < wgs; ++w) {
+    order[w] = w;
+    key[w] = (items * w / wgs) % period;
+  }
+  if (sb_xcd_order_enabled())
+    std::stable_sort(order, order + wgs, [&](int a, int b) { return key[a] < key[b]; });
+  const int base = wgs / 8, extra = wgs % 8;
+  for (int b = 0; b < wgs; ++b) {
+    const int x = b % 8, j = b / 8;
+    share_of[b] = (unsigned short)order[x * base + std::min(x, extra) + j];
+  }
+}
+
 template <int NT, int WM, int ROLE>
 static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const char* name) {
   constexpr int STAGES = WM == 4 ? 2 : (NT == 4 ? 3 : 4);
@@ -467,8 +496,8 @@ __device__ inline bf16x8 sb_pair_frag(const unsigned int* tile, int ldw, int p0,
 // rows a 16-lane group reads fall into different banks.
 //
 // Work items are (output tile of BMQ x BNX, slab), tile major; every workgroup takes an equal
-// contiguous share, writes one fp32 partial tile per output tile it touched, and
-// project_sum_kernel adds the partial tiles of each output tile in workgroup order.
+// contiguous share (share_of says which), writes one fp32 partial tile per output tile it touched,
+// and project_sum_kernel adds the partial tiles of each output tile in the order of the shares.
 
 
 struct ProjectArgs {
@@ -489,6 +518,7 @@ struct ProjectArgs {
   int segs_max;            // partial tiles reserved per workgroup
   int bmq, bnx;            // rows and columns of an output tile
   int stream_x;            // X is too large to stay cached: copy it non-temporally
+  unsigned short share_of[SB_MAX_WGS];   // share of the items that workgroup B takes (wgs entries)
 };
 
 #define PJ_MAX_PARTS 40   // partial tiles per output tile: the launcher keeps it at 32 + 2 boundary shares
@@ -535,8 +565,9 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
     q_off[i] = X_BYTES + frow * QPITCH + (((col >> 3) ^ (2 * (s16 >> 2))) << 4) + (col & 7) * 2;
   }
 
-  const int64_t item_begin = g.items * blockIdx.x / gridDim.x;
-  const int64_t item_end = g.items * (blockIdx.x + 1) / gridDim.x;
+  const int share = g.share_of[blockIdx.x];
+  const int64_t item_begin = g.items * share / gridDim.x;
+  const int64_t item_end = g.items * (share + 1) / gridDim.x;
   int64_t item = item_begin;
   int seg = 0;
   while (item < item_end) {
@@ -647,7 +678,7 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
     sb_barrier_keep_copies();                        // the stages may be refilled by a next segment
 
     // partial tile: rows = columns of Q, columns = columns of X
-    float* dst = g.part + ((int64_t)blockIdx.x * g.segs_max + seg) * (BMQ * BNX);
+    float* dst = g.part + ((int64_t)share * g.segs_max + seg) * (BMQ * BNX);
 #pragma unroll
     for (int i = 0; i < NTQ; ++i)
 #pragma unroll
@@ -664,13 +695,13 @@ __global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
   }
 }
 
-// V tile blockIdx.y = sum of the partial tiles that cover it, in workgroup order; a thread owns
-// groups of 4 consecutive columns.  The workgroup range of the tile is uniform per block.
+// V tile blockIdx.y = sum of the partial tiles that cover it, in the order of the shares; a thread owns
+// groups of 4 consecutive columns.  The range of shares of the tile is uniform per block.
 template <int LPG>   // lanes per output group: 4 when an output tile has many partial tiles, else 1
 __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
   const int64_t tile = blockIdx.y;
   const int64_t lo_item = tile * g.slabs, hi_item = lo_item + g.slabs;
-  // first workgroup whose share [items w / wgs, items (w+1) / wgs) reaches into the tile
+  // first share [items w / wgs, items (w+1) / wgs) that reaches into the tile
   int64_t w_lo = lo_item * g.wgs / g.items;
   while (g.items * (w_lo + 1) / g.wgs <= lo_item) ++w_lo;
   int64_t w_hi = w_lo;                               // exclusive
@@ -818,6 +849,8 @@ static int launch_project_mfma(hipStream_t s, ProjectArgs g, const char* name = 
   // basis, which every column block re-reads, out of L2 -- measured at 8192 x 11008: twice the
   // algorithmic bytes fetched, 108 -> 103 us)
   g.stream_x = sb_streams_past_cache(g.m * g.n * 2, 128);
+  if (g.wgs > SB_MAX_WGS) return LORACT_ERR_UNSUPPORTED;
+  sb_xcd_share_order(g.items, g.wgs, g.slabs, g.share_of);
   int rc = launch_project_main(s, g, name, role);
   if (rc != LORACT_OK) return rc;
   return launch_project_sum(s, g);
@@ -854,6 +887,7 @@ struct ReconArgs {
   int64_t items;         // column blocks * row_tiles
   int bn;                // columns per block
   int stream_out;        // Xhat is too large to stay cached: store it non-temporally
+  unsigned short share_of[SB_MAX_WGS];   // share of the items that workgroup B takes
 };
 
 
@@ -905,8 +939,9 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
     }
   };
 
-  const int64_t item_begin = g.items * blockIdx.x / gridDim.x;
-  const int64_t item_end = g.items * (blockIdx.x + 1) / gridDim.x;
+  const int share = g.share_of[blockIdx.x];
+  const int64_t item_begin = g.items * share / gridDim.x;
+  const int64_t item_end = g.items * (share + 1) / gridDim.x;
   int64_t item = item_begin;
   while (item < item_end) {
     // ---- segment: the items of one column block
@@ -1081,6 +1116,7 @@ static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
   // as many workgroups as stay resident: LDS allows 160 KB per CU, registers about 2 per CU
   const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)reconstruct_lds_bytes(nks)));
   const int64_t wgs = std::min<int64_t>(g.items, 256 * per_cu);
+  sb_xcd_share_order(g.items, (int)wgs, g.row_tiles, g.share_of);
   dim3 grid((unsigned)wgs);
   switch (nks) {
 #define RC_CASE(N) case N: return launch_reconstruct_nks<N>(s, g, grid);
