@@ -521,7 +521,7 @@ struct ProjectArgs {
   unsigned short share_of[SB_MAX_WGS];   // share of the items that workgroup B takes (wgs entries)
 };
 
-#define PJ_MAX_PARTS 40   // partial tiles per output tile: the launcher keeps it at 32 + 2 boundary shares
+#define PJ_MAX_PARTS 72   // partial tiles per output tile: the launcher keeps it at 64 + 2 boundary shares
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 
@@ -765,7 +765,9 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
 // partial tiles are small against X) eight waves on 256 columns with two stages.
 static inline void project_shape_for(int l, int64_t m, int64_t n, int* ntq, int* ntx, int* stages, int* wn) {
   *wn = 2;
-  if (l <= 64) { *ntq = 1; *ntx = 2; *stages = 2; }
+  // (a single column block, as in the LoRA gradient: 64-column tiles of Q, so that the workgroups
+  // that share the rows of a tall Q are four times as many -- one CU pulls only about 28 GB/s)
+  if (l <= 64 || n <= 128) { *ntq = 1; *ntx = 2; *stages = 2; }
   else if (l <= 128) { *ntq = 2; *ntx = 2; *stages = 2; }
   else if (m < 32768 || n < 1024) { *ntq = 4; *ntx = 2; *stages = 3; }   // (a narrow X, as in the LoRA gradient, has no use for 256-column tiles)
   else { *ntq = 4; *ntx = 2; *stages = 2; *wn = 4; }
@@ -786,8 +788,9 @@ static void project_plan(ProjectArgs* g) {
   const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)project_lds_bytes(ntq, ntx, stages, wn)));
   // at least 4 slabs per workgroup: a partial tile costs as much as a slab to write and sum
   int64_t wgs = std::min<int64_t>(256 * per_cu, ceil_div64(g->items, 4));
-  // and at most 32 partial tiles per output tile: the sum walks them one after the other
-  wgs = std::min<int64_t>(wgs, 32 * tiles);
+  // and at most 32 partial tiles per output tile (64 for a single column block, where the grid
+  // would otherwise be a few dozen workgroups): the sum walks them one after the other
+  wgs = std::min<int64_t>(wgs, (g->n <= 128 ? 64 : 32) * tiles);
   wgs = std::max<int64_t>(1, std::min<int64_t>(wgs, g->items));
   // hard bound the sum kernel relies on: shares of floor(items / wgs) slabs or more put at most
   // ceil(slabs / share) + 1 partial tiles on an output tile
@@ -820,7 +823,7 @@ static int launch_project_shape(hipStream_t s, const ProjectArgs& g, const char*
 
 template <int ROLE>
 static int launch_project_role(hipStream_t s, const ProjectArgs& g, const char* name) {
-  if (g.l <= 64) return launch_project_shape<1, 2, 2, 2, ROLE>(s, g, name);
+  if (g.l <= 64 || g.n <= 128) return launch_project_shape<1, 2, 2, 2, ROLE>(s, g, name);
   if (g.l <= 128) return launch_project_shape<2, 2, 2, 2, ROLE>(s, g, name);
   if (g.m < 32768 || g.n < 1024) return launch_project_shape<4, 2, 3, 2, ROLE>(s, g, name);
   return launch_project_shape<4, 2, 2, 4, ROLE>(s, g, name);
