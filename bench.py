@@ -56,7 +56,8 @@ def algorithmic_cost(name: str, m: int, n: int, k: int, b: int, n_out: int, r: i
     if name in hbm:
         return "hbm", float(hbm[name]), "GB/s"
     flops = {
-        "gram": 2.0 * m * kp * kp * 0.75,        # lower 64-blocks only
+        # the lower 64 x 64 blocks of the kp x kp matrix, diagonal included
+        "gram": 2.0 * m * 4096.0 * (((kp + 63) // 64) * ((kp + 63) // 64 + 1) // 2),
         "trsm_apply": 1.0 * m * kp * kp + 2.0 * m * kp * 16,
         "chol": kp ** 3 / 3.0,
         # factorisation and triangular solve of a round in one launch (round 2 usually ends at once:

@@ -1459,8 +1459,8 @@ static int launch_chol_trsm_fused_nj(hipStream_t s, const CholArgs& c, const Trs
   const int ptld = chol_reg_ptld(c.kp);
   // At least 81 KB: one workgroup per CU, so that the factorising workgroup -- whose first wave is
   // the critical path of the whole launch -- never shares its CU's issue slots with solving
-  // workgroups (measured at 65536 rows: 235 us with two workgroups per CU, against 139 us for the two
-  // separate launches).
+  // workgroups (measured at 65536 rows, 256 columns: 235 us with two workgroups per CU, 206 us with
+  // one).
   const size_t lds = std::max<size_t>(std::max(chol_reg_lds_bytes(c.kp), trsm_lds_bytes<NJ, CR_THREADS / 64, true>()),
                                       81 * 1024);
   static std::atomic<bool> attr_done{false};
