@@ -50,21 +50,28 @@ def block_sumsq(a: np.ndarray, bm: int = 64, bn: int = 128) -> np.ndarray:
     return np.add.reduceat(rows, np.arange(0, a.shape[1], bn), axis=1)
 
 
-def check_local(got: np.ndarray, want: np.ndarray, un: np.ndarray, vn: np.ndarray, tol: float,
-                eps: float, what: str) -> dict:
+def check_local(got: np.ndarray, want: np.ndarray, un: np.ndarray, cn: np.ndarray, tol: float,
+                eps: float, what: str, row_floor: float = 0.0) -> dict:
     """Local agreement of a reconstruction with the oracle's, so that a misplaced or missing
     tile cannot hide inside a global norm.
 
     (i)  every 64 x 128 block (the tile a workgroup of the streaming kernels owns): relative
          Frobenius error <= tol, relative to the block's own norm in the oracle (blocks whose
          oracle norm is below 1e-3 of the average block are measured against that floor);
-    (ii) every element: |got - want| <= 4 eps ||u_i|| ||v_c|| + eps |want|, where u_i and v_c
-         are the row of U and the column of V the element is the inner product of (both from the
-         oracle; these norms do not depend on the choice of basis) and eps is the unit rounding
-         of the storage type of the factors (2^-8 for bf16: each factor entry carries 2^-9, the
-         stored element another 2^-9).  By Cauchy-Schwarz that is what entrywise rounding of U
-         and V can move an element by, with a factor four of slack for what is not rounding
-         (the finite accuracy of the basis).
+    (ii) every element: |got - want| <= 4 eps ||u_i|| ||x_c|| + eps |want| + row_floor ||x_c||,
+         where u_i is the row of U the element is formed from (oracle value; its norm does not
+         depend on the choice of basis), x_c the column of X that column c of V = U^T X is the
+         image of (`cn`, its norm), and eps the unit rounding of the storage type of the factors
+         (2^-8 for bf16: each factor entry carries 2^-9, the stored element another 2^-9).
+         Entrywise rounding of U moves v_c = U^T x_c by up to eps ||x_c|| -- not eps ||v_c||: a
+         column of which the basis captures little is a cancellation -- and of V by eps ||v_c|| <=
+         eps ||x_c||; by Cauchy-Schwarz the element moves by ||u_i|| times that, with a factor four
+         of slack for what is not rounding (the finite accuracy of the basis).  For columns that
+         the basis captures well ||v_c|| ~ ||x_c|| and nothing is given away.  `row_floor` is an
+         absolute error of a row of U that does not shrink with the row: the bf16 path
+         accumulates the sketch in float32, so a row of the basis is resolved to about 2^-20 of
+         the typical row norm however small the row itself is (a row nearly orthogonal to the
+         sampled rows is a cancellation too).  Both cancellations are met with k = 1.
     """
     d = got - want
     err = np.sqrt(block_sumsq(d))
@@ -73,7 +80,7 @@ def check_local(got: np.ndarray, want: np.ndarray, un: np.ndarray, vn: np.ndarra
     rel = err / np.maximum(ref, floor)
     worst = np.unravel_index(int(np.argmax(rel)), rel.shape)
     assert rel.max() <= tol, "%s: block %s relative error %.3e > %.1e" % (what, worst, rel.max(), tol)
-    bound = 4.0 * eps * np.outer(un, vn) + eps * np.abs(want) + 1e-300
+    bound = 4.0 * eps * np.outer(un, cn) + eps * np.abs(want) + row_floor * cn[None, :] + 1e-300
     ratio = np.abs(d) / bound
     at = np.unravel_index(int(np.argmax(ratio)), ratio.shape)
     assert ratio.max() <= 1.0, "%s: element %s off by %.3e, bound %.3e" % (what, at, abs(d[at]), bound[at])
@@ -144,8 +151,11 @@ def check_compress_parity(w: synth.Workload, u_gpu: torch.Tensor, v_gpu: torch.T
         # bf16 inputs: the basis enters the projection rounded to bf16 whatever type the factors
         # are returned in, so the unit rounding of the comparison is that of bf16 storage
         eps = 2.0 ** -8 if (bf16_factors or w.dtype == "bf16") else 2.0 ** -20
-        un, vn = np.linalg.norm(uo_r, axis=1), np.linalg.norm(vo, axis=0)
-        loc = check_local(rebuilt, xo, un, vn, tol, eps, "U V rebuilt on the host")
+        un = np.linalg.norm(uo_r, axis=1)
+        cn = np.sqrt(np.einsum("ij,ij->j", w.x, w.x, dtype=np.float64))     # column norms of X
+        # float32 accumulation of the sketch: absolute resolution of a row of the basis
+        row_floor = 2.0 ** -20 * float(np.sqrt(np.mean(un * un))) if w.dtype == "bf16" else 0.0
+        loc = check_local(rebuilt, xo, un, cn, tol, eps, "U V rebuilt on the host", row_floor)
         res["block_max_factors"], res["elem_factors"] = loc["block_max"], loc["elem_max_over_bound"]
     del rebuilt
     if xhat_gpu is not None:
@@ -154,6 +164,6 @@ def check_compress_parity(w: synth.Workload, u_gpu: torch.Tensor, v_gpu: torch.T
         assert res["parity_reconstruct"] <= tol, res
         if local:
             eps_out = eps if xhat_gpu.dtype != torch.bfloat16 else max(eps, 2.0 ** -8)
-            loc = check_local(xh, xo, un, vn, tol, eps_out, "GPU reconstruction")
+            loc = check_local(xh, xo, un, cn, tol, eps_out, "GPU reconstruction", row_floor)
             res["block_max_reconstruct"], res["elem_reconstruct"] = loc["block_max"], loc["elem_max_over_bound"]
     return res

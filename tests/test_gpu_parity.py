@@ -83,8 +83,10 @@ def test_fp32_exact_rank_is_recovered():
 
 
 @pytest.mark.parametrize("m,n,k", [(64, 64, 8), (333, 200, 24), (1000, 520, 70), (130, 203, 17),
-                                    (2050, 96, 96), (97, 1031, 33), (515, 264, 130)])
+                                    (2050, 96, 96), (97, 1031, 33), (515, 264, 130), (1795, 410, 1)])
 def test_bf16_small_and_ragged_shapes(m, n, k):
+    # (rank 1: U is the normalised sketch column itself, so rows nearly orthogonal to the sampled
+    # row show the float32 accumulation of the sketch undiluted)
     w = _spectrum_workload(m, n, k, seed=3 * m + n + k, dtype="bf16")
     x, u, v, xhat, status = _run(w)
     of = orc.decompose(w.x.astype(np.float64), w.k, seed=w.seed)
@@ -95,7 +97,7 @@ def test_bf16_small_and_ragged_shapes(m, n, k):
 
 @pytest.mark.parametrize("m,n,k", [(130, 64, 17), (1000, 512, 72), (4100, 1024, 136), (520, 640, 264),
                                     (777, 320, 320), (129, 128, 128), (2048, 192, 8), (385, 448, 200),
-                                    (1500, 512, 250), (600, 256, 16), (700, 256, 33)])
+                                    (1500, 512, 250), (600, 256, 16), (700, 256, 33), (602, 1024, 1)])
 def test_bf16_streaming_kernels_ragged_rows_and_all_rank_tiles(m, n, k):
     # n % 64 == 0 selects the matrix-core streaming kernels; the shapes walk through every
     # accumulator-tile variant (kp <= 64, <= 128, <= 256, two column blocks), the maximum rank,
