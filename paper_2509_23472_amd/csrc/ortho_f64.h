@@ -1256,8 +1256,20 @@ struct NsPolyArgs {
 };
 
 __device__ inline bool ns_poly_active(const NsPolyArgs& g, int lane) {
+  // lane i adds shares i, i + 64, ... in that order; eight loads at a time are in flight (from
+  // clamped indices, masked at use), or the loop is a chain of as many memory latencies
   double part_sum = 0.0;
-  for (int w = lane; w < g.e2_count; w += 64) part_sum += g.e2[w];
+  for (int w0 = lane; w0 < g.e2_count; w0 += 512) {
+    double v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int w = w0 + 64 * u;
+      v[u] = g.e2[w < g.e2_count ? w : g.e2_count - 1];
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (w0 + 64 * u < g.e2_count) part_sum += v[u];
+  }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) part_sum += __shfl_xor(part_sum, off);
   return part_sum > g.lo_tol * g.lo_tol && part_sum <= g.hi_tol * g.hi_tol;
