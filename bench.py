@@ -164,7 +164,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=10)
-    ap.add_argument("--workload", default="c3", choices=["c2a", "c2b", "c3", "c4", "c5", "coherent", "c5stream"])
+    ap.add_argument("--workload", default="c3", choices=["c1", "c2a", "c2b", "c3", "c4", "c5", "coherent", "c5stream"])
     ap.add_argument("--layers", type=int, default=32,
                     help="c5stream only: decoder layers to stream (7 sites each; the configuration is 32 layers, "
                          "fewer is a subsample of it and is labelled so)")
@@ -204,7 +204,11 @@ def main() -> int:
     else:
         w = synth.FULL_SIZE[args.workload]()
     m, n, k = w.m, w.n, w.k
-    b = 2
+    # config 1 is float32 (float64 accumulation on the device); the others are bf16
+    is_f32 = w.dtype == "f32"
+    b = 4 if is_f32 else 2
+    dt = torch.float32 if is_f32 else torch.bfloat16
+    dt_name = "f32" if is_f32 else "bf16"
     rng = np.random.default_rng(123)
     dy_h = w.extras.get("dY")
     bl_h = w.extras.get("B_lora")
@@ -215,12 +219,14 @@ def main() -> int:
     r_l, n_out = bl_h.shape[0], dy_h.shape[1]
 
     def up(a):
+        if is_f32:
+            return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
         return torch.from_numpy(synth.f32_to_bf16_bits(a).view(np.int16)).cuda().view(torch.bfloat16)
 
     x, dy, bl = up(w.x), up(dy_h), up(bl_h)
-    u = torch.empty((m, k), dtype=torch.bfloat16, device="cuda")
-    v = torch.empty((k, n), dtype=torch.bfloat16, device="cuda")
-    xhat = torch.empty((m, n), dtype=torch.bfloat16, device="cuda")
+    u = torch.empty((m, k), dtype=dt, device="cuda")
+    v = torch.empty((k, n), dtype=dt, device="cuda")
+    xhat = torch.empty((m, n), dtype=dt, device="cuda")
     ga = torch.empty((n, r_l), dtype=torch.float32, device="cuda")
 
     def compress():
@@ -392,7 +398,7 @@ def main() -> int:
     # the eager result (the library records kernels only: no copies, no memsets, ids in the kernel
     # arguments), with eager work and synchronisations between replays.
     pipelined_graph = None
-    if not args.no_comparator:
+    if not args.no_comparator and not is_f32:
         nstreams = min(args.streams, 4)
         streams = [torch.cuda.Stream() for _ in range(nstreams)]
         gheld, graphs = [], []
@@ -543,9 +549,9 @@ def main() -> int:
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": "%s: %dx%d bf16, rank %d, LoRA rank %d, dY %dx%d; step = compress + "
-                               "reconstruct + lora_grad" % (args.workload, m, n, k, r_l, m, n_out)},
+        "dtype": dt_name, "data": "synthetic",
+        "config": {"workload": "%s: %dx%d %s, rank %d, LoRA rank %d, dY %dx%d; step = compress + "
+                               "reconstruct + lora_grad" % (args.workload, m, n, dt_name, k, r_l, m, n_out)},
         "phases_us": {"compress": round(us_c, 1), "reconstruct": round(us_r, 1), "lora_grad": round(us_l, 1)},
         "phases_us_cold_cache": {"compress": round(us_c_cold, 1), "reconstruct": round(us_r_cold, 1),
                                  "lora_grad": round(us_l_cold, 1),
