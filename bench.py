@@ -348,6 +348,11 @@ def main() -> int:
     roofline = {"kernel": dom, "bound": d_bound, "achieved": round(achieved, 2), "peak": peak,
                 "unit": d_unit, "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_us": round(d_avg_s * 1e6, 2), "algorithmic_per_launch": d_amount}
+    if dom in ("chol_trsm", "chol"):
+        # a chain of k dependent pivots on one CU (the triangular solve runs beside it in the same
+        # launch): priced against the float64 vector peak only because the line wants a number
+        roofline["note"] = ("latency-bound: k sequential pivots on one CU, solve hidden behind them; "
+                            "roofline_streaming is the bandwidth-bound figure")
 
     # the slowest HBM-streaming kernel as well (the dominant kernel may be a latency-bound one)
     streaming = {kn: kv for kn, kv in kernels.items() if kv["bound"] == "hbm" and kv["achieved"]}
