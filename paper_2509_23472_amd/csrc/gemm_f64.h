@@ -6,7 +6,8 @@
 //
 // Operand addressing as in gemm_bf16.h (K-contiguous with optional row indirection for B, or
 // K-strided); element types are chosen at run time (fp32, bf16 or fp64).  One 256-thread
-// workgroup computes a 64 x 64 tile, K in slabs of 16 through LDS, 4 x 4 outputs per thread.
+// workgroup computes a 64 x 64 tile, K in slabs of 16 through LDS (the next slab is fetched into
+// registers while the current one is multiplied), 4 x 4 outputs per thread.
 // blockIdx.z splits K into fp64 partial tiles that reduce_partials_f64 sums in a fixed order.
 #pragma once
 #include "common.h"
@@ -31,28 +32,47 @@ struct GemmF64Args {
 #define GD_BN 64
 #define GD_BK 16
 
-__device__ inline void gd_load_tile(double (*Ls)[GD_BM + 1], const void* P, int64_t ld,
-                                    const int32_t* rows, int kc, int ek, int64_t row0,
-                                    int64_t nrows, int64_t k0, int64_t kend, int t) {
+// Element (i, kk) of a 64 x 16 operand slab that thread t handles in its step s; K-contiguous
+// operands are walked along K by neighbouring threads, K-strided ones along the rows.
+__device__ inline void gd_slot(int kc, int t, int s, int* i, int* kk) {
+  const int e = t + 256 * s;
+  if (kc) { *kk = e & 15; *i = e >> 4; } else { *i = e & 63; *kk = e >> 6; }
+}
+// The four elements of a slab that a thread brings in.  The loads are unconditional, from indices
+// clamped into the matrix (a load under a branch would be waited for on the spot); what lies
+// outside is replaced by zero when the values are put into LDS.
+template <int EK>
+__device__ inline double gd_load(const void* p, int64_t i) {
+  if (EK == EK_F32) return (double)((const float*)p)[i];
+  if (EK == EK_F64) return ((const double*)p)[i];
+  return (double)(float)((const bf16_t*)p)[i];
+}
+template <int EK>
+__device__ inline void gd_fetch_tile(double* v, const void* P, int64_t ld, const int32_t* rows, int kc,
+                                     int64_t row0, int64_t nrows, int64_t k0, int64_t kend, int t) {
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
-    const int e = t + 256 * s;
     int i, kk;
-    if (kc) { kk = e & 15; i = e >> 4; } else { i = e & 63; kk = e >> 6; }
-    const int64_t gr = row0 + i, gk = k0 + kk;
-    double v = 0.0;
-    if (gr < nrows && gk < kend) {
-      if (kc) {
-        const int64_t src_row = rows ? (int64_t)rows[gr] : gr;
-        v = load_f64(P, src_row * ld + gk, ek);
-      } else {
-        v = load_f64(P, gk * ld + gr, ek);
-      }
-    }
-    Ls[kk][i] = v;
+    gd_slot(kc, t, s, &i, &kk);
+    int64_t gr = row0 + i, gk = k0 + kk;
+    if (gr > nrows - 1) gr = nrows - 1;
+    if (gk > kend - 1) gk = kend - 1;
+    const int64_t src_row = (kc && rows) ? (int64_t)rows[gr] : gr;     // (does not depend on the slab)
+    v[s] = gd_load<EK>(P, kc ? src_row * ld + gk : gk * ld + gr);
+  }
+}
+__device__ inline void gd_put_tile(double (*Ls)[GD_BM + 1], const double* v, int kc, int64_t row0,
+                                   int64_t nrows, int64_t k0, int64_t kend, int t) {
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    int i, kk;
+    gd_slot(kc, t, s, &i, &kk);
+    Ls[kk][i] = (row0 + i < nrows && k0 + kk < kend) ? v[s] : 0.0;
   }
 }
 
+// AEK, BEK: element kinds of the operands (compiled in, so that the loads are not under a branch).
+template <int AEK, int BEK>
 __global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64Args g) {
   __shared__ double As[GD_BK][GD_BM + 1];
   __shared__ double Bs[GD_BK][GD_BN + 1];
@@ -69,10 +89,17 @@ __global__ __launch_bounds__(256) void gemm_f64_kernel(GemmF64Args g) {
 #pragma unroll
     for (int j = 0; j < 4; ++j) acc[i][j] = 0.0;
 
+  // the next slab is on its way to registers while the current one is multiplied
+  double va[4], vb[4];
+  gd_fetch_tile<AEK>(va, g.A, g.lda, nullptr, g.a_kc, row0, g.M, kbeg, kend, t);
+  gd_fetch_tile<BEK>(vb, g.B, g.ldb, g.b_rows, g.b_kc, col0, g.N, kbeg, kend, t);
   for (int64_t k0 = kbeg; k0 < kend; k0 += GD_BK) {
-    gd_load_tile(As, g.A, g.lda, nullptr, g.a_kc, g.a_ek, row0, g.M, k0, kend, t);
-    gd_load_tile(Bs, g.B, g.ldb, g.b_rows, g.b_kc, g.b_ek, col0, g.N, k0, kend, t);
+    gd_put_tile(As, va, g.a_kc, row0, g.M, k0, kend, t);
+    gd_put_tile(Bs, vb, g.b_kc, col0, g.N, k0, kend, t);
     __syncthreads();
+    // (after the last slab this fetches clamped elements that nobody uses)
+    gd_fetch_tile<AEK>(va, g.A, g.lda, nullptr, g.a_kc, row0, g.M, k0 + GD_BK, kend, t);
+    gd_fetch_tile<BEK>(vb, g.B, g.ldb, g.b_rows, g.b_kc, col0, g.N, k0 + GD_BK, kend, t);
 #pragma unroll
     for (int kk = 0; kk < GD_BK; ++kk) {
       double a[4], b[4];
@@ -138,7 +165,14 @@ static int launch_gemm_f64(const char* name, hipStream_t stream, const void* A, 
   g.k_per_split = kps;
   dim3 grid((unsigned)ceil_div64(M, GD_BM), (unsigned)ceil_div64(N, GD_BN), (unsigned)splits);
   if (grid.y > 65535 || grid.z > 65535) return LORACT_ERR_UNSUPPORTED;
-  LORACT_LAUNCH(name, stream, gemm_f64_kernel, grid, dim3(256), 0, g);
+  // one instantiation per pair of operand kinds
+#define GD_CASE(AE, BE) \
+  if (a_ek == AE && b_ek == BE) { LORACT_LAUNCH(name, stream, (gemm_f64_kernel<AE, BE>), grid, dim3(256), 0, g); } else
+  GD_CASE(EK_F32, EK_F32) GD_CASE(EK_F32, EK_F64) GD_CASE(EK_F32, EK_BF16)
+  GD_CASE(EK_F64, EK_F32) GD_CASE(EK_F64, EK_F64) GD_CASE(EK_F64, EK_BF16)
+  GD_CASE(EK_BF16, EK_F32) GD_CASE(EK_BF16, EK_F64) GD_CASE(EK_BF16, EK_BF16)
+  return LORACT_ERR_INVALID_ARG;
+#undef GD_CASE
   if (splits > 1) {
     const int64_t total = M * N;
     int blocks = (int)(ceil_div64(total, 256) < 2048 ? ceil_div64(total, 256) : 2048);

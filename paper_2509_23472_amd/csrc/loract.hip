@@ -91,6 +91,7 @@ struct Plan {
   size_t off_idx, off_a, off_b, off_ub, off_g, off_rinv, off_dpart, off_fpart, off_zt;
   size_t off_bmat, off_eig, off_omega, off_dinv, off_q1b, off_nsT, off_gbak, off_flag;
   int sketch_splits, bgram_splits;
+  int sketch64_splits;    // K splits of the sketch on the float64 path
   size_t total;
 };
 
@@ -125,8 +126,8 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl, bool truncate_
   pl->kp = (l + 15) / 16 * 16;
   const size_t ybytes = pl->bf16_path ? (size_t)m * pl->kp * 4 : (size_t)m * l * 8;
   const int64_t lt = ceil_div64(l, 64);
-  pl->gram_splits = pick_splits(lt * lt, m, 256);
-  pl->proj_splits = pick_splits(lt * ceil_div64(n, 64), m, 256);
+  pl->gram_splits = pick_splits(lt * lt, m, 64);
+  pl->proj_splits = pick_splits(lt * ceil_div64(n, 64), m, 64);
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
   pl->off_idx = take(sizeof(int32_t) * LORACT_MAX_RANK);
@@ -142,6 +143,9 @@ static int make_plan(const loract_params* p, bool rsvd, Plan* pl, bool truncate_
   pl->off_flag = take(64 + 8 * (64 * 16 + 128));   // flag word, up to 64 x 15 shares of ||E||^2, 100 of ||E^4||^2
   size_t dpart = (size_t)pl->gram_splits * l * l * 8;
   if (!pl->bf16_path) dpart = std::max(dpart, (size_t)pl->proj_splits * l * n * 8);
+  // the float64 sketch splits the hidden dimension while the row tiles alone leave CUs idle
+  pl->sketch64_splits = pl->bf16_path ? 1 : pick_splits(ceil_div64(m, 64) * lt, n, 64);
+  if (pl->sketch64_splits > 1) dpart = std::max(dpart, (size_t)pl->sketch64_splits * m * l * 8);
   if (pl->bf16_path) dpart = std::max(dpart, gram_partial_bytes(m, pl->kp));
   if (pl->bf16_path) dpart = std::max(dpart, (size_t)pl->kp * pl->kp * 8);   // E^2 of the degree-4 finish
   const bool trunc = l > p->k || truncate_always;
@@ -213,7 +217,8 @@ static int sketch(const Ctx& c, const void* Bt, int64_t ldb, const int32_t* rows
                             ldb, 1, rows, m, l, n, Y, c.pl.kp, EK_F32, 1, nullptr, c.pl.kp);
   }
   return launch_gemm_f64("sketch_f64", c.s, c.X, c.p->ldx, 1, EK_F32, Bt, ldb, 1,
-                         rows ? EK_F32 : EK_F64, rows, m, l, n, 1.0, Y, l, EK_F64, 1, nullptr);
+                         rows ? EK_F32 : EK_F64, rows, m, l, n, 1.0, Y, l, EK_F64, c.pl.sketch64_splits,
+                         ws_ptr<double>(c, c.pl.off_dpart));
 }
 
 // Thin QR of Y (m x l) by two rounds of Cholesky QR with float64 Gram matrices (the orthonormalisations
@@ -603,7 +608,7 @@ static int make_lora_plan(int64_t m, int64_t n, int32_t k, int64_t n_out, int32_
   if (m < 1 || n < 1 || k < 1 || n_out < 1 || r < 1 || r > 64) return LORACT_ERR_INVALID_ARG;
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-  lp->t_splits = pick_splits(ceil_div64(k, 64), m, 128);
+  lp->t_splits = pick_splits(ceil_div64(k, 64), m, 64);
   lp->rp = (r + 15) / 16 * 16;
   lp->g_splits = sketch_splits_for(m, n_out, lp->rp);
   lp->off_g = take((size_t)m * lp->rp * 4);
