@@ -382,6 +382,8 @@ static inline bool sb_aligned(const void* p, int64_t ld) {
 // of that operand at about the same time and fetch each of them into their L2 once, instead of once
 // per workgroup.  share_of[B] = share of workgroup B; any permutation is correct, this one is fast.
 #define SB_MAX_WGS 512
+// Tuning knob for measurements: LORACT_XCD_ORDER=0 in the environment deals the shares out in
+// their natural order instead.
 static bool sb_xcd_order_enabled() {
   static const bool on = [] { const char* e = getenv("LORACT_XCD_ORDER"); return !(e && e[0] == '0'); }();
   return on;

@@ -258,7 +258,12 @@ def test_reconstruct_alone_on_given_factors(dtype):
 
 @pytest.mark.parametrize("dtype,m,n,k,n_out,r", [("bf16", 777, 256, 32, 320, 16),
                                                   ("bf16", 300, 136, 20, 75, 5),
-                                                  ("f32", 260, 96, 12, 130, 8)])
+                                                  ("f32", 260, 96, 12, 130, 8),
+                                                  # matrix-core path with several 64-column tiles of U
+                                                  # and many row shares, ragged rows, wide LoRA rank
+                                                  ("bf16", 4100, 512, 256, 384, 16),
+                                                  ("bf16", 9000, 320, 136, 256, 64),
+                                                  ("bf16", 2111, 256, 72, 128, 33)])
 def test_lora_grad_matches_oracle(dtype, m, n, k, n_out, r):
     L = _lib()
     w = _spectrum_workload(m, n, k, seed=m + r, dtype=dtype)
