@@ -20,9 +20,7 @@
 #pragma once
 #include "common.h"
 
-#define SB_BM 128
-#define SB_BK 64
-#define SB_LDT 72   // bf16 elements per LDS row of a [row][K] tile (64 + 8 pad)
+#define SB_BK 64     // contraction slab of the sketch and the projection
 
 // Split reductions (over K in the sketch, over the rows in the projection) leave fp32 partial
 // tiles in a scratch buffer; this kernel sums them in ascending split order, so the result does
