@@ -336,15 +336,16 @@ def main() -> int:
         achieved, peak = d_amount / d_avg_s / 1e12, FP64_VECTOR_PEAK_TFLOPS
     # HBM bytes per launch from the committed rocprofv3 --pmc summary, only if that summary was taken
     # from this very build of the library (same source hash); otherwise null
-    traffic = None
+    traffic, traffic_of = None, {}
     if os.path.exists(args.traffic_json):
         try:
             from paper_2509_23472_amd.build import source_hash
             tj = json.load(open(args.traffic_json))
             if tj.get("source_hash") == source_hash():
-                traffic = tj.get(args.workload, {}).get(dom)
+                traffic_of = tj.get(args.workload, {})
+                traffic = traffic_of.get(dom)
         except Exception:
-            traffic = None
+            traffic, traffic_of = None, {}
     roofline = {"kernel": dom, "bound": d_bound, "achieved": round(achieved, 2), "peak": peak,
                 "unit": d_unit, "frac": round(achieved / peak, 4), "traffic": traffic,
                 "avg_us": round(d_avg_s * 1e6, 2), "algorithmic_per_launch": d_amount}
@@ -364,6 +365,7 @@ def main() -> int:
         roofline_streaming = {"kernel": sn, "bound": "hbm", "achieved": round(s_amount / s_avg / 1e9, 2),
                               "peak": HBM_PEAK_GBS, "unit": "GB/s",
                               "frac": round(s_amount / s_avg / 1e9 / HBM_PEAK_GBS, 4),
+                              "traffic": traffic_of.get(sn),
                               "avg_us": round(s_avg * 1e6, 2), "algorithmic_per_launch": s_amount}
 
     # several independent sites in flight on separate HIP streams (as the sites of a layer are in
