@@ -894,18 +894,26 @@ struct ReconArgs {
 };
 
 
-// NKS = number of 16-deep K steps = ceil(k / 16).  Four waves.  WIDE = false: 128 columns per
+// NKS = number of 16-deep K steps = ceil(k / 16).  WIDE = false: four waves, 128 columns per
 // block, waves 2 (64-column groups) x 2 (32-row halves).  WIDE = true (for k > 128, where a
-// workgroup fills a CU's LDS anyway): 256 columns per block, one 64-column group per wave and both
-// row halves -- half the U traffic and half the barriers per byte written, and every U fragment
-// feeds four matrix instructions instead of two.
+// workgroup fills a CU's LDS anyway): eight waves, 256 columns per block, every wave 32 columns and
+// both row halves -- half the U traffic and half the barriers per byte written.  With 32 columns
+// a wave's V fragments take 64 registers instead of 128, so that two waves fit on a SIMD, and the
+// copies and stores of a tile are issued by eight waves side by side (a wave gets a 1 KB memory
+// instruction out only every ~150 clocks): 77 -> 64 us at 8192 x 11008 against four waves of 64
+// columns.  The price is that every U fragment read from LDS feeds two matrix instructions instead
+// of four: at k = 256 the LDS reads of a tile (8 waves x 32 KB) take as long as its matrix
+// instructions, which is what bounds this kernel now (two independent workgroups per CU on
+// 128-column blocks, with the staging tile swizzled instead of padded to fit 2 x 80 KB, were slower:
+// 204 against 170 us at 65536 x 4096).
 template <int NKS, bool WIDE>
-__global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
-  constexpr int NW = 4, NT = 256;               // waves, threads
-  constexpr int WN = WIDE ? 4 : 2;              // 64-column groups
+__global__ __launch_bounds__(WIDE ? 512 : 256) void reconstruct_mfma_kernel(ReconArgs g) {
+  constexpr int NW = WIDE ? 8 : 4, NT = 64 * NW;   // waves, threads
+  constexpr int WN = WIDE ? 4 : 2;              // 64-column groups of the block
+  constexpr int CT = WIDE ? 1 : 2;              // 32-column tiles per wave
   constexpr int RH = WIDE ? 2 : 1;              // 32-row halves per wave
-  constexpr int NST = 2 * WN;                   // 16-byte stores per thread and tile
   constexpr int BN = 64 * WN;
+  constexpr int NST = RC_BM * (BN / 8) / NT;    // 16-byte stores per thread and tile
   constexpr int LDC = BN + 8;                   // bf16 elements per row of the output staging tile
   constexpr int CS_BYTES = RC_BM * LDC * 2;
   constexpr int CPR = 2 * NKS;                  // 16-byte chunks per U row in LDS
@@ -917,7 +925,7 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
   unsigned int* Vs = (unsigned int*)sb_smem;                       // [NKS * 8][RC_LDV], prologue only
 
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int wm = WIDE ? wave : wave >> 1;       // 64-column group
+  const int wc = WIDE ? wave * 32 : (wave >> 1) * 64;   // first column of the wave inside the block
   const int wn = WIDE ? 0 : wave & 1;           // first 32-row half
   const int cvalid = g.k >> 3;                  // valid chunks per row (k is a multiple of 8)
   const bf16x8 zero8 = {(bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f, (bf16_t)0.0f,
@@ -956,7 +964,7 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
     const int64_t col0 = cb * BN;
 
     // this wave's V fragments (64 columns of Xhat, all K steps), staged 128 columns at a time
-    bf16x8 a[NKS][2];
+    bf16x8 a[NKS][CT];
 #pragma unroll
     for (int h = 0; h < WN / 2; ++h) {
       __syncthreads();   // LDS is free: a previous segment (or half) is done with it
@@ -974,12 +982,12 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
         *(u32x4*)(d + 4) = w1;
       }
       __syncthreads();
-      if (WN == 2 || (wm >> 1) == h) {
+      if (WN == 2 || (wc >> 7) == h) {
 #pragma unroll
         for (int ks = 0; ks < NKS; ++ks)
 #pragma unroll
-          for (int i = 0; i < 2; ++i)
-            a[ks][i] = sb_pair_frag(Vs, RC_LDV, ks * 8 + 4 * (lane >> 5), (wm & 1) * 64 + 32 * i + (lane & 31));
+          for (int i = 0; i < CT; ++i)
+            a[ks][i] = sb_pair_frag(Vs, RC_LDV, ks * 8 + 4 * (lane >> 5), (wc & 127) + 32 * i + (lane & 31));
       }
     }
     __syncthreads();   // the V staging area is free: it overlaps Cs and the U buffers
@@ -1006,9 +1014,9 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
       sb_barrier_lds();   // copies of all waves landed; previous tile's reads of Cs are complete
 
       const unsigned char* ub = Ub + cur * UBUF;
-      f32x16 acc[2][RH];
+      f32x16 acc[CT][RH];
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < CT; ++i)
 #pragma unroll
         for (int j = 0; j < RH; ++j)
 #pragma unroll
@@ -1041,16 +1049,16 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
           const int ks = GS * gi + u;
           if (ks < NKS) {
 #pragma unroll
-            for (int j = 0; j < RH; ++j) {
-              acc[0][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][0], b[gi & 1][u][j], acc[0][j], 0, 0, 0);
-              acc[1][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][1], b[gi & 1][u][j], acc[1][j], 0, 0, 0);
-            }
+            for (int j = 0; j < RH; ++j)
+#pragma unroll
+              for (int i = 0; i < CT; ++i)
+                acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[ks][i], b[gi & 1][u][j], acc[i][j], 0, 0, 0);
           }
         }
       }
       // accumulator register r of lane l: column 8*(r/4) + 4*(l/32) + r%4 of Xhat, row l%32
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < CT; ++i)
 #pragma unroll
         for (int j = 0; j < RH; ++j)
 #pragma unroll
@@ -1058,7 +1066,7 @@ __global__ __launch_bounds__(256) void reconstruct_mfma_kernel(ReconArgs g) {
             bf16x4 o;
 #pragma unroll
             for (int u = 0; u < 4; ++u) o[u] = (bf16_t)acc[i][j][4 * q + u];
-            const int col = wm * 64 + 32 * i + 8 * q + 4 * (lane >> 5);
+            const int col = wc + 32 * i + 8 * q + 4 * (lane >> 5);
             *(bf16x4*)(Cs + (urow + 32 * j) * LDC + col) = o;
           }
       sb_barrier_lds();
@@ -1105,7 +1113,7 @@ static int launch_reconstruct_nks(hipStream_t s, const ReconArgs& g, dim3 grid) 
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(reconstruct LDS)");
     attr_done.store(true, std::memory_order_release);
   }
-  LORACT_LAUNCH("reconstruct", s, (reconstruct_mfma_kernel<NKS, WIDE>), grid, dim3(256), lds, g);
+  LORACT_LAUNCH("reconstruct", s, (reconstruct_mfma_kernel<NKS, WIDE>), grid, dim3(WIDE ? 512 : 256), lds, g);
   return LORACT_OK;
 }
 
