@@ -143,19 +143,27 @@ struct SketchArgs {
 // 0 the sketch of Algorithm 1, 1 the product dY B_lora^T of the LoRA gradient, 2 the finish of
 // the orthonormalisation.  The code is the same.
 enum { SK_SKETCH = 0, SK_LORA_DYB = 1, SK_NS_CORRECT = 2 };
-template <int NT, int STAGES, int WM, int ROLE>
-__global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
+// RT = 32-row tiles per wave: 2 (a wave owns 64 rows), or 1 (32 rows: twice the waves on the same
+// tile -- half the accumulators per wave and the copies of a slab issued by twice as many waves;
+// used for the 128-row tiles of up to 128 columns: sketch 23.1 -> 21.7 us and the Newton-Schulz
+// finish 11.9 -> 9.2 us at 8192 x 4096 with 128 columns, dY B^T 16.5 -> 15.3 us; and for the
+// finish on 256-row tiles, 42.6 -> 38.3 us at 65536 x 256, where the sketch itself is no faster
+// on sixteen waves than on eight).
+template <int NT, int STAGES, int WM, int ROLE, int RT = 2>
+__global__ __launch_bounds__(256 * WM / RT) void sketch_mfma_kernel(SketchArgs g) {
   constexpr int BM = 64 * WM, BN = 64 * NT;
-  constexpr int NB = 4 * NT / WM;       // Bt copy instructions per wave per slab
+  constexpr int NWV = 4 * WM / RT;      // waves: BM / (32 RT) row groups x 2 column halves
+  constexpr int NA = 8 * WM / NWV;      // X copy instructions per wave per slab (8 rows each)
+  constexpr int NB = 8 * NT / NWV;      // Bt copy instructions per wave per slab
   constexpr int A_BYTES = BM * 128, B_BYTES = BN * 128, STAGE_BYTES = A_BYTES + B_BYTES;
-  constexpr int LOADS = 4 + NB;         // wave-level copy instructions per slab per wave
+  constexpr int LOADS = NA + NB;        // wave-level copy instructions per slab per wave
   extern __shared__ __attribute__((aligned(16))) unsigned char sb_smem[];
   const int run_mode = g.run_flag ? *g.run_flag : 1;
   if (g.fin_q ? run_mode == 0 : run_mode != 1) return;
   if (g.fin_q && run_mode == 2) {
     // no product: the whole grid converts fin_q1, four columns per thread and step
-    const int64_t nthreads = (int64_t)gridDim.x * gridDim.y * gridDim.z * (128 * WM);
-    const int64_t tid = (((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * (128 * WM) + threadIdx.x;
+    const int64_t nthreads = (int64_t)gridDim.x * gridDim.y * gridDim.z * (64 * NWV);
+    const int64_t tid = (((int64_t)blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x) * (64 * NWV) + threadIdx.x;
     const int c4 = g.kp >> 2;
     const bool vec_ok = (g.fin_ld & 3) == 0 && ((uintptr_t)g.fin_q & 15) == 0 && ((uintptr_t)g.fin_qb & 7) == 0;
     const int64_t total = g.m * c4;
@@ -223,10 +231,10 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   // accumulator rows / columns that are never stored)
   const int sub = lane >> 3;                       // row within the 8-row group = row & 7
   const int kc = (lane & 7) ^ sub;                 // swizzled K chunk fetched by this lane
-  const bf16_t* a_src[4];
+  const bf16_t* a_src[NA];
 #pragma unroll
-  for (int i = 0; i < 4; ++i) {
-    int64_t r = row0 + (wave * 4 + i) * 8 + sub;
+  for (int i = 0; i < NA; ++i) {
+    int64_t r = row0 + (wave * NA + i) * 8 + sub;
     if (r >= g.m) r = g.m - 1;
     a_src[i] = g.X + r * g.ldx + kbeg + kc * 8;
   }
@@ -245,27 +253,27 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
     if (pos >= nslab) pos -= nslab;
     const int64_t koff = (int64_t)pos * SB_BK;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (g.stream_x) sb_async16_stream(a_src[i] + koff, st + (wave * 4 + i) * 1024);
-      else sb_async16(a_src[i] + koff, st + (wave * 4 + i) * 1024);
+    for (int i = 0; i < NA; ++i) {
+      if (g.stream_x) sb_async16_stream(a_src[i] + koff, st + (wave * NA + i) * 1024);
+      else sb_async16(a_src[i] + koff, st + (wave * NA + i) * 1024);
     }
 #pragma unroll
     for (int i = 0; i < NB; ++i)
       sb_async16(b_src[i] + koff, st + A_BYTES + (wave * NB + i) * 1024);
   };
 
-  f32x16 acc[2][NT];
+  f32x16 acc[RT][NT];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < RT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j)
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
 
   // fragment addresses inside a stage
-  int a_off[2], b_off[NT];
+  int a_off[RT], b_off[NT];
 #pragma unroll
-  for (int i = 0; i < 2; ++i) a_off[i] = (wm * 64 + 32 * i + (lane & 31)) * 128;
+  for (int i = 0; i < RT; ++i) a_off[i] = (wm * 32 * RT + 32 * i + (lane & 31)) * 128;
 #pragma unroll
   for (int j = 0; j < NT; ++j) b_off[j] = A_BYTES + (wn * 32 * NT + 32 * j + (lane & 31)) * 128;
   const int rsw = lane & 7;                        // (row & 7) of every fragment row of this lane
@@ -284,13 +292,13 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       const int pos = ((2 * ks + khalf) ^ rsw) << 4;
-      bf16x8 a[2], b[NT];
+      bf16x8 a[RT], b[NT];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) a[i] = *(const bf16x8*)(st + a_off[i] + pos);
+      for (int i = 0; i < RT; ++i) a[i] = *(const bf16x8*)(st + a_off[i] + pos);
 #pragma unroll
       for (int j = 0; j < NT; ++j) b[j] = *(const bf16x8*)(st + b_off[j] + pos);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < RT; ++i)
 #pragma unroll
         for (int j = 0; j < NT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[i], b[j], acc[i][j], 0, 0, 0);
@@ -300,7 +308,7 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   // epilogue: accumulator register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32
   if (g.fin_q) {
 #pragma unroll
-    for (int i = 0; i < 2; ++i)
+    for (int i = 0; i < RT; ++i)
 #pragma unroll
       for (int j = 0; j < NT; ++j) {
         const int col = col0 + wn * 32 * NT + 32 * j + (lane & 31);
@@ -309,7 +317,7 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
         int64_t rows[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
-          const int64_t row = row0 + wm * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+          const int64_t row = row0 + wm * 32 * RT + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
           rows[r] = row;
           q1[r] = g.fin_q1[(row < g.m ? row : g.m - 1) * g.kp + col];
         }
@@ -326,7 +334,7 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
   }
   float* dst = g.splits > 1 ? g.part + (int64_t)zsplit * g.m * g.kp : g.Y;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < RT; ++i)
 #pragma unroll
     for (int j = 0; j < NT; ++j) {
       const int col = col0 + wn * 32 * NT + 32 * j + (lane & 31);
@@ -334,7 +342,7 @@ __global__ __launch_bounds__(128 * WM) void sketch_mfma_kernel(SketchArgs g) {
       const bool live = col < g.l;
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
-        const int64_t row = row0 + wm * 64 + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+        const int64_t row = row0 + wm * 32 * RT + 32 * i + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
         if (row < g.m) dst[row * g.kp + col] = live ? acc[i][j][r] : 0.0f;
       }
     }
@@ -402,18 +410,18 @@ static void sb_xcd_share_order(int64_t items, int wgs, int64_t period, unsigned 
   }
 }
 
-template <int NT, int WM, int ROLE>
+template <int NT, int WM, int ROLE, int RT = 2>
 static int launch_sketch_nt(hipStream_t s, const SketchArgs& g, dim3 grid, const char* name) {
   constexpr int STAGES = WM == 4 ? 2 : (NT == 4 ? 3 : 4);
   static std::atomic<bool> attr_done{false};
   const size_t lds = sketch_lds_bytes(NT, WM);
   if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, STAGES, WM, ROLE>,
+    hipError_t e = hipFuncSetAttribute((const void*)sketch_mfma_kernel<NT, STAGES, WM, ROLE, RT>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(sketch LDS)");
     attr_done.store(true, std::memory_order_release);
   }
-  LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, STAGES, WM, ROLE>), grid, dim3(128 * WM), lds, g);
+  LORACT_LAUNCH(name, s, (sketch_mfma_kernel<NT, STAGES, WM, ROLE, RT>), grid, dim3(256 * WM / RT), lds, g);
   return LORACT_OK;
 }
 
@@ -439,13 +447,13 @@ static int launch_sketch_mfma(hipStream_t s, SketchArgs g, const char* name = "s
   const int role = g.fin_q ? SK_NS_CORRECT : (split_out ? SK_LORA_DYB : SK_SKETCH);
 #define SK_LAUNCH(ROLE)                                                                                   \
   switch (nt) {                                                                                           \
-    case 1: rc = launch_sketch_nt<1, 2, ROLE>(s, g, grid, name); break;                                   \
-    case 2: rc = launch_sketch_nt<2, 2, ROLE>(s, g, grid, name); break;                                   \
-    default: rc = wm == 4 ? launch_sketch_nt<4, 4, ROLE>(s, g, grid, name)                                \
+    case 1: rc = launch_sketch_nt<1, 2, ROLE, 1>(s, g, grid, name); break;                                \
+    case 2: rc = launch_sketch_nt<2, 2, ROLE, 1>(s, g, grid, name); break;                                \
+    default: rc = wm == 4 ? launch_sketch_nt<4, 4, ROLE, (ROLE == SK_NS_CORRECT ? 1 : 2)>(s, g, grid, name) \
                           : launch_sketch_nt<4, 2, ROLE>(s, g, grid, name); break;                        \
   }
   if (role == SK_NS_CORRECT) { SK_LAUNCH(SK_NS_CORRECT) }
-  else if (role == SK_LORA_DYB && nt == 1) rc = launch_sketch_nt<1, 2, SK_LORA_DYB>(s, g, grid, name);
+  else if (role == SK_LORA_DYB && nt == 1) rc = launch_sketch_nt<1, 2, SK_LORA_DYB, 1>(s, g, grid, name);
   else { SK_LAUNCH(SK_SKETCH) }
 #undef SK_LAUNCH
   if (rc != LORACT_OK) return rc;
@@ -529,15 +537,19 @@ __device__ inline s16x4 sb_read_tr(const unsigned char* lds_ptr) {
   return __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)lds_ptr);
 }
 
-// Output tile (64 NTQ) x (32 NTX WN), waves 2 x WN, each with NTQ x NTX matrix-core tiles.
+// Output tile (32 NTQ WQ) x (32 NTX WN), waves WQ x WN, each with NTQ x NTX matrix-core tiles.
 // WN = 4 (8 waves, 256 columns of X for NTX = 2) halves the re-reads of Q per byte of X.
+// WQ = 4 (8 waves on the same tile as WQ = 2 with twice the NTQ): half the accumulators per wave,
+// so two waves fit on a SIMD, and the copies of a slab are issued by eight waves side by side (a
+// wave gets a 1 KB copy out only every ~150 clocks): 95 -> 81 us at 8192 x 11008 with 256 columns
+// of Q, 24 -> 21.7 us at 8192 x 4096 with 128.
 // ROLE only names the use in the kernel's symbol: 0 the projection V = Q^T X, 1 the product
 // U^T [G_hi | G_lo] of the LoRA gradient.
 enum { PJ_PROJECT = 0, PJ_LORA_UTG = 1 };
-template <int NTQ, int NTX, int STAGES, int WN, int ROLE>
-__global__ __launch_bounds__(128 * WN) void project_mfma_kernel(ProjectArgs g) {
-  constexpr int NW = 2 * WN;                       // waves
-  constexpr int BMQ = 64 * NTQ, BNX = 32 * NTX * WN;
+template <int NTQ, int NTX, int STAGES, int WN, int ROLE, int WQ = 2>
+__global__ __launch_bounds__(64 * WQ * WN) void project_mfma_kernel(ProjectArgs g) {
+  constexpr int NW = WQ * WN;                      // waves: WQ along the columns of Q x WN along those of X
+  constexpr int BMQ = 32 * NTQ * WQ, BNX = 32 * NTX * WN;
   constexpr int CQ = BMQ / 8, CX = BNX / 8;        // 16-byte chunks per slab row
   constexpr int QPITCH = BMQ * 2, XPITCH = BNX * 2;
   constexpr int X_BYTES = SB_BK * XPITCH, Q_BYTES = SB_BK * QPITCH;
@@ -759,10 +771,11 @@ __global__ __launch_bounds__(256) void project_sum_kernel(ProjectArgs g) {
   }
 }
 
-// Tile shape and ring depth.  Up to 128 columns of Q: 128-column tiles with a two-stage ring, so
-// that two workgroups share a CU (one hides the other's waits) and the partial tiles stay small.
-// Wider Q: one workgroup per CU, three stages of 128 columns, or for tall matrices (where the
-// partial tiles are small against X) eight waves on 256 columns with two stages.
+// Tile shape and ring depth (bmq = 64 ntq whatever the wave layout is; the launcher picks the
+// layout).  Up to 128 columns of Q: 128-column tiles with a two-stage ring, so that two workgroups
+// share a CU (one hides the other's waits) and the partial tiles stay small.  Wider Q: one
+// workgroup per CU, three stages of 128 columns, or for tall matrices (where the partial tiles
+// are small against X) 256 columns with two stages.  All but the narrowest run eight waves.
 static inline void project_shape_for(int l, int64_t m, int64_t n, int* ntq, int* ntx, int* stages, int* wn) {
   *wn = 2;
   // (a single column block, as in the LoRA gradient: 64-column tiles of Q, so that the workgroups
@@ -807,25 +820,25 @@ static size_t project_part_floats(int64_t m, int64_t n, int l) {
   return (size_t)g.wgs * g.segs_max * g.bmq * g.bnx;
 }
 
-template <int NTQ, int NTX, int STAGES, int WN, int ROLE>
+template <int NTQ, int NTX, int STAGES, int WN, int ROLE, int WQ = 2>
 static int launch_project_shape(hipStream_t s, const ProjectArgs& g, const char* name) {
   static std::atomic<bool> attr_done{false};
-  const size_t lds = project_lds_bytes(NTQ, NTX, STAGES, WN);
+  const size_t lds = project_lds_bytes(NTQ * WQ / 2, NTX, STAGES, WN);
   if (lds > 64 * 1024 && !attr_done.load(std::memory_order_acquire)) {
-    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES, WN, ROLE>,
+    hipError_t e = hipFuncSetAttribute((const void*)project_mfma_kernel<NTQ, NTX, STAGES, WN, ROLE, WQ>,
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     if (e != hipSuccess) return hip_fail(e, "hipFuncSetAttribute(project LDS)");
     attr_done.store(true, std::memory_order_release);
   }
-  LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES, WN, ROLE>), dim3((unsigned)g.wgs), dim3(128 * WN), lds, g);
+  LORACT_LAUNCH(name, s, (project_mfma_kernel<NTQ, NTX, STAGES, WN, ROLE, WQ>), dim3((unsigned)g.wgs), dim3(64 * WQ * WN), lds, g);
   return LORACT_OK;
 }
 
 template <int ROLE>
 static int launch_project_role(hipStream_t s, const ProjectArgs& g, const char* name) {
   if (g.l <= 64 || g.n <= 128) return launch_project_shape<1, 2, 2, 2, ROLE>(s, g, name);
-  if (g.l <= 128) return launch_project_shape<2, 2, 2, 2, ROLE>(s, g, name);
-  if (g.m < 32768 || g.n < 1024) return launch_project_shape<4, 2, 3, 2, ROLE>(s, g, name);
+  if (g.l <= 128) return launch_project_shape<1, 2, 2, 2, ROLE, 4>(s, g, name);
+  if (g.m < 32768 || g.n < 1024) return launch_project_shape<2, 2, 3, 2, ROLE, 4>(s, g, name);
   return launch_project_shape<4, 2, 2, 4, ROLE>(s, g, name);
 }
 static int launch_project_main(hipStream_t s, const ProjectArgs& g, const char* name, int role) {
