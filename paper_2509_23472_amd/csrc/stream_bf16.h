@@ -1140,6 +1140,7 @@ static int launch_reconstruct_mfma(hipStream_t s, ReconArgs g) {
   // as many workgroups as stay resident: LDS allows 160 KB per CU, registers about 2 per CU
   const int64_t per_cu = std::max<int64_t>(1, std::min<int64_t>(2, (160 * 1024) / (int64_t)reconstruct_lds_bytes(nks)));
   const int64_t wgs = std::min<int64_t>(g.items, 256 * per_cu);
+  if (wgs > SB_MAX_WGS) return LORACT_ERR_UNSUPPORTED;     // (share_of has SB_MAX_WGS entries)
   sb_xcd_share_order(g.items, (int)wgs, g.row_tiles, g.share_of);
   dim3 grid((unsigned)wgs);
   switch (nks) {
